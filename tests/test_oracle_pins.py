@@ -1,0 +1,275 @@
+"""Pins for the CPU checker: brute force, automaton invariants, the worked
+example, the closed-form identity for the dynamic cursor and the amortised move
+bound.  None of these retypes the checker's own procedure."""
+import os
+
+import numpy as np
+import pytest
+
+from bruteforce import endpos_classes, first_end, longest_suffix_match, substrings
+from oracle.sam_oracle import Batch, Sam, Sequence
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "abcbc.txt")
+
+
+def _rand_text(rng, n, vocab, copy=True):
+    x = rng.integers(0, vocab, size=n).tolist()
+    if copy and n > 8:
+        for _ in range(max(1, n // 12)):
+            l = int(rng.integers(2, 7))
+            i = int(rng.integers(l, n - l + 1)) if n - l + 1 > l else l
+            j = int(rng.integers(0, i - l + 1))
+            x[i:i + l] = x[j:j + l]
+    return x[:n]
+
+
+def _cases():
+    out = []
+    for seed in range(60):
+        rng = np.random.default_rng(1000 + seed)
+        vocab = [2, 3, 4, 32000][seed % 4]
+        n = int(rng.integers(1, 70))
+        out.append((seed, vocab, n))
+    return out
+
+
+def _parse_golden():
+    sec, data = None, {}
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        if line.startswith("["):
+            sec = line.strip("[]")
+            data[sec] = []
+            continue
+        data[sec].append(line.split())
+    return data
+
+
+def _structure(sam):
+    link, length, endpos, n_next = sam.states()
+    src, tok, dst = sam.transitions()
+    nxt = [dict() for _ in range(sam.num_states)]
+    for s, t, d in zip(src.tolist(), tok.tolist(), dst.tolist()):
+        nxt[s][t] = d
+    return link.tolist(), length.tolist(), endpos.tolist(), nxt
+
+
+# --------------------------------------------------------------------------
+# worked example (Figure 2's string)
+
+def test_abcbc_table():
+    g = _parse_golden()
+    text = [0, 1, 2, 1, 2]
+    sam = Sam.build(text)
+    link, length, endpos, nxt = _structure(sam)
+    assert sam.num_states == int(g["totals"][0][0])
+    assert sam.num_trans == int(g["totals"][0][1])
+    for row in g["states"]:
+        i = int(row[0])
+        assert (length[i], link[i], endpos[i]) == (int(row[1]), int(row[2]), int(row[3]))
+        want = {int(a.split(":")[0]): int(a.split(":")[1]) for a in row[4:]}
+        assert nxt[i] == want
+    distinct = sum(length[v] - length[link[v]] for v in range(1, sam.num_states))
+    assert distinct == int(g["totals"][0][2]) == len(substrings(text))
+
+
+def _draft_of(field):
+    return [] if field == "-" else [int(v) for v in field.split(",")]
+
+
+def test_abcbc_dynamic_and_static_walks():
+    g = _parse_golden()
+    text = [0, 1, 2, 1, 2]
+    seq = Sequence(None, None)
+    for tok, row in zip(text, g["dynamic"]):
+        seq.feed([tok])
+        d = seq.draft(2)
+        assert d["match_len"] == int(row[0])
+        assert seq.cursors()[2] == int(row[1])
+        assert d["draft"][:d["draft_len"]].tolist() == _draft_of(row[2])
+        assert (d["draft"][d["draft_len"]:] == -1).all()
+    corpus = np.array(text, dtype=np.int32)
+    st = Sam.build(corpus)
+    link, length, endpos, _ = _structure(st)
+    seq = Sequence(st, corpus)
+    # l_bias large and negative is not needed: read the static cursor directly
+    for tok, row in zip([2, 1, 2, 0], g["static CBCA"]):
+        seq.feed([tok])
+        s1, l1, _, _ = seq.cursors()
+        assert (l1, s1, endpos[s1]) == (int(row[0]), int(row[1]), int(row[2]))
+        want = _draft_of(row[3])
+        assert corpus[endpos[s1]:endpos[s1] + 4].tolist() == want
+
+
+# --------------------------------------------------------------------------
+# the automaton against the definition of its states
+
+@pytest.mark.parametrize("seed,vocab,n", _cases())
+def test_states_are_endpos_classes(seed, vocab, n):
+    rng = np.random.default_rng(seed)
+    text = _rand_text(rng, n, vocab)
+    sam = Sam.build(text)
+    link, length, endpos, nxt = _structure(sam)
+    info = endpos_classes(text)
+    # identity of a state that does not depend on numbering: (length, first end)
+    keys = [(length[v], endpos[v]) for v in range(sam.num_states)]
+    assert len(set(keys)) == len(keys)
+    assert set(keys) == set(info.keys())
+    for v, key in enumerate(keys):
+        d = info[key]
+        assert (None if link[v] < 0 else keys[link[v]]) == d["link"]
+        assert {t: keys[u] for t, u in nxt[v].items()} == d["next"]
+        # the longest string of the state is text[endpos-len : endpos)
+        assert tuple(text[endpos[v] - length[v]:endpos[v]]) == d["longest"]
+    # counting bounds
+    if n >= 2:
+        assert sam.num_states <= 2 * n - 1
+    if n >= 3:
+        assert sam.num_trans <= 3 * n - 4
+    assert all(length[link[v]] < length[v] for v in range(1, sam.num_states))
+    assert sum(length[v] - length[link[v]] for v in range(1, sam.num_states)) == len(substrings(text))
+    assert sum(len(d) for d in nxt) == sam.num_trans
+
+
+@pytest.mark.parametrize("seed,vocab,n", _cases()[:24])
+def test_invariants_hold_after_every_expand(seed, vocab, n):
+    rng = np.random.default_rng(50 + seed)
+    text = _rand_text(rng, n, vocab)
+    sam = Sam()
+    for k, t in enumerate(text, 1):
+        sam.expand(t)
+        link, length, endpos, nxt = _structure(sam)
+        assert length[sam.last] == k and endpos[sam.last] == k
+        for v in range(1, sam.num_states):
+            assert length[link[v]] < length[v] <= endpos[v] <= k
+            w = text[endpos[v] - length[v]:endpos[v]]
+            assert first_end(text[:k], w) == endpos[v]
+            # shortest string of the class first ends there as well
+            ws = w[len(w) - length[link[v]] - 1:]
+            assert first_end(text[:k], ws) == endpos[v]
+
+
+# --------------------------------------------------------------------------
+# matching against the definition of the result
+
+@pytest.mark.parametrize("seed,vocab,n", _cases())
+def test_static_and_dynamic_match_brute_force(seed, vocab, n):
+    rng = np.random.default_rng(77 + seed)
+    corpus = _rand_text(rng, n, vocab)
+    m = int(rng.integers(1, 60))
+    x = _rand_text(rng, m, vocab)
+    # make the sequence share material with the corpus
+    if n > 6 and m > 6:
+        l = min(6, n, m)
+        i = int(rng.integers(0, m - l + 1))
+        j = int(rng.integers(0, n - l + 1))
+        x[i:i + l] = corpus[j:j + l]
+    L = int(rng.integers(1, 9))
+    l_bias = int(rng.integers(0, 3))
+    carr = np.array(corpus, dtype=np.int32)
+    st = Sam.build(carr)
+    _, _, endpos1, _ = _structure(st)
+    seq = Sequence(st, carr)
+    for t in range(1, m + 1):
+        seq.feed([x[t - 1]])
+        s1, l1, s2, l2 = seq.cursors()
+        k1, e1 = longest_suffix_match(corpus, x[:t])
+        k2, e2 = longest_suffix_match(x, x[:t], limit=t - 1)
+        assert l1 == k1
+        assert l2 == k2
+        if k1:
+            assert endpos1[s1] == e1
+        d = seq.draft(L, l_bias)
+        if k1 > k2 + l_bias:
+            want_src, ml, T, p, Tn = 2, k1, corpus, e1, n
+        else:
+            want_src, ml, T, p, Tn = 1, k2, x, e2, t
+        if ml == 0:
+            assert (d["source"], d["match_len"], d["draft_len"]) == (0, 0, 0)
+            assert (d["draft"] == -1).all()
+            continue
+        want = list(T[p:min(p + L, Tn)])
+        assert d["source"] == want_src and d["match_len"] == ml and d["endpos"] == p
+        assert d["draft"][:d["draft_len"]].tolist() == want
+        assert (d["draft"][d["draft_len"]:] == -1).all()
+    c = seq.counters()
+    assert c["identity_violations"] == 0
+    # amortised bound of Appendix A.3: link moves <= tokens, next moves <= tokens
+    assert c["static_link_hops"] <= m and c["static_next_moves"] <= m
+    assert c["dynamic_link_hops"] <= m and c["dynamic_next_moves"] <= m
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_dynamic_equals_static_on_prefix(seed):
+    """The dynamic result at time t equals a static walk of x[0..t) over an
+    automaton built on x[0..t-1)."""
+    rng = np.random.default_rng(300 + seed)
+    x = _rand_text(rng, int(rng.integers(2, 40)), [2, 3, 5][seed % 3])
+    seq = Sequence(None, None)
+    for t in range(1, len(x) + 1):
+        seq.feed([x[t - 1]])
+        _, _, s2, l2 = seq.cursors()
+        ref = Sam.build(x[:t - 1])
+        _, _, ep, _ = _structure(ref)
+        s, l = 0, 0
+        for tok in x[:t]:
+            s, l = ref.transfer(tok, s, l)
+        assert l == l2
+        if l:
+            dl, dn, de, _ = _structure(seq.dynamic())
+            assert de[s2] == ep[s]
+
+
+def test_dynamic_cursor_is_link_of_last_on_long_input():
+    rng = np.random.default_rng(5)
+    x = _rand_text(rng, 4000, 3)
+    seq = Sequence(None, None)
+    seq.feed(x)
+    c = seq.counters()
+    assert c["identity_violations"] == 0 and c["canon_hops"] > 0
+    dyn = seq.dynamic()
+    link, length, _, _ = _structure(dyn)
+    _, _, s2, l2 = seq.cursors()
+    assert s2 == link[dyn.last] and l2 == length[s2]
+    assert dyn.num_states <= 2 * len(x) - 1 and dyn.num_trans <= 3 * len(x) - 4
+
+
+def test_unseen_token_resets_to_root_and_empty_cases():
+    corpus = np.array([1, 2, 3, 1, 2], dtype=np.int32)
+    st = Sam.build(corpus)
+    seq = Sequence(st, corpus)
+    seq.feed([1, 2])
+    assert seq.cursors()[:2][1] == 2
+    seq.feed([9])
+    assert seq.cursors()[:2] == (0, 0)
+    d = seq.draft(4)
+    assert d["source"] == 0 and d["draft_len"] == 0
+    # feeding nothing changes nothing
+    before = seq.cursors()
+    seq.feed([])
+    assert seq.cursors() == before
+    # empty corpus automaton is just a root
+    assert Sam.build([]).num_states == 1
+
+
+def test_batch_matches_single_sequences():
+    rng = np.random.default_rng(9)
+    corpus = np.array(_rand_text(rng, 300, 6), dtype=np.int32)
+    st = Sam.build(corpus)
+    B, A, L = 5, 4, 6
+    prompts = [np.array(_rand_text(rng, 20, 6), dtype=np.int32) for _ in range(B)]
+    batch = Batch(st, corpus, prompts, A, L, 0)
+    singles = [Sequence(st, corpus) for _ in range(B)]
+    for s, p in zip(singles, prompts):
+        s.feed(p)
+    for _ in range(10):
+        counts = rng.integers(0, A + 1, size=B).astype(np.int32)
+        acc = rng.integers(0, 6, size=(B, A)).astype(np.int32)
+        ml, src, dl, d = batch.step(acc, counts)
+        for b in range(B):
+            singles[b].feed(acc[b, :counts[b]])
+            r = singles[b].draft(L, 0)
+            assert (ml[b], src[b], dl[b]) == (r["match_len"], r["source"], r["draft_len"])
+            assert (d[b] == r["draft"]).all()
