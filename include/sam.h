@@ -1,0 +1,186 @@
+/*
+ * sam.h - C ABI of the batched suffix-automaton draft library for AMD gfx950.
+ *
+ * The library implements the retrieval path of SAM-Decoding (arxiv 2411.10666):
+ * for a batch of independent decoding sequences it keeps, in device memory,
+ *   - one static suffix automaton built over a token corpus (Section 3.1), and
+ *   - one dynamic suffix automaton per sequence, extended online with that
+ *     sequence's own tokens (Section 3.1, Section 3.3),
+ * and, per generation round, pushes the newly accepted tokens through both
+ * (Transfer, Algorithm 1; Expand, Algorithm 2), picks the source by match
+ * length (Section 3.2, "static only if l1 > l2 + l_bias") and reads the next
+ * draft_len tokens after the earliest end position of the match (Section 3.2,
+ * d = T[p+1 : p+n]).
+ *
+ * Conventions
+ *   - Tokens are int32 in [0, vocab).  Arrays are 0-indexed and row-major.
+ *   - "host" / "device" on a pointer says where the memory must live.  Device
+ *     pointers are plain HIP device addresses on the current device.
+ *   - States are numbered in the creation order of Algorithm 2: root 0; per
+ *     token the new state, then the clone if one is made.
+ *   - A state's end position is the paper's 1-indexed min_endpos (a prefix
+ *     length), so the draft is the 0-indexed slice T[p : p+draft_len).
+ *   - Every function returns SAM_OK (0) or a negative error code and never
+ *     throws; sam_last_error() gives a thread-local message for the last
+ *     failure on the calling thread.
+ *   - Calls that take a stream enqueue work on it and return without waiting,
+ *     except where a comment says the call synchronises.  `hip_stream` is a
+ *     hipStream_t passed as void* (NULL = the default stream).
+ *   - The caller owns all input and output buffers.  The library owns the two
+ *     opaque handles and everything behind them.  A sam_corpus is immutable
+ *     after sam_build and may be shared by any number of batches; it must
+ *     outlive them.  Calls on one sam_batch must not overlap in time.
+ */
+#ifndef SAM_H_
+#define SAM_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SAM_OK          0
+#define SAM_EINVAL     -1   /* bad argument (null pointer, size out of range)   */
+#define SAM_ENOMEM     -2   /* host or device allocation failed                 */
+#define SAM_ECAPACITY  -3   /* a sequence would grow past max_seq_len           */
+#define SAM_ETOKEN     -4   /* a token outside [0, vocab)                       */
+#define SAM_EDEVICE    -5   /* a HIP call failed                                */
+
+/* bits of the device-side status word (sam_batch_status) */
+#define SAM_STATUS_CAPACITY  1u   /* some sequence hit max_seq_len; it was not advanced */
+#define SAM_STATUS_TOKEN     2u   /* some sequence saw a token outside [0, vocab); that
+                                     token and the rest of its row were not fed         */
+#define SAM_STATUS_COUNT     4u   /* some count was < 0 or > max_accept; sequence skipped */
+#define SAM_STATUS_INTERNAL  8u   /* a table walk hit its safety bound (corrupted tables,
+                                     e.g. overlapping calls on one batch); results invalid */
+
+/* values written to `source` */
+#define SAM_SOURCE_NONE     0   /* match_len == 0, no draft */
+#define SAM_SOURCE_DYNAMIC  1
+#define SAM_SOURCE_STATIC   2
+
+typedef struct sam_corpus sam_corpus;
+typedef struct sam_batch  sam_batch;
+
+const char *sam_last_error(void);
+
+/*
+ * Build-SAM (Algorithm 2) over `corpus_tokens` on the host, then copy the
+ * automaton to device memory as flat arrays: the corpus text, one
+ * {link, length(link)} record per state, a direct-indexed table of the root's
+ * transitions and a bucketed open-addressed (state, token) -> {target,
+ * min_endpos(target)} hash for all other transitions.
+ *   corpus_tokens : host, int32 [n_tokens]; a multi-document corpus is passed
+ *                   already joined by a separator token (Section 3.1).
+ *   n_tokens      : 1 .. 2^31-2.   vocab : 1 .. 2^31-1.
+ *   out           : receives the handle; free it with sam_corpus_free.
+ * Synchronises.  Errors: SAM_EINVAL, SAM_ETOKEN (a corpus token outside the
+ * vocabulary), SAM_ENOMEM, SAM_EDEVICE.
+ */
+int sam_build(const int32_t *corpus_tokens, int64_t n_tokens, int32_t vocab,
+              sam_corpus **out);
+
+/*
+ * Same host construction as sam_build but nothing is copied to a device, so it
+ * runs on a machine without a GPU.  The handle can be inspected
+ * (sam_corpus_info / _export / _find) but not used by sam_batch_init.
+ */
+int sam_build_host_only(const int32_t *corpus_tokens, int64_t n_tokens, int32_t vocab,
+                        sam_corpus **out);
+
+/* Counts of the built automaton and bytes of device memory it occupies
+ * (0 for a host-only handle).  Any output pointer may be NULL. */
+int sam_corpus_info(const sam_corpus *corpus, int64_t *n_states, int64_t *n_trans,
+                    int64_t *device_bytes);
+
+/*
+ * Copy the host-side state table out, for inspection: length, link (-1 for the
+ * root) and min_endpos per state, each host int32 [n_states].  Any may be NULL.
+ */
+int sam_corpus_export(const sam_corpus *corpus, int32_t *length, int32_t *link,
+                      int32_t *min_endpos);
+
+/* Host lookup of one transition through the same tables the device uses:
+ * *target = next(state)[token], or -1 if there is none. */
+int sam_corpus_find(const sam_corpus *corpus, int64_t state, int32_t token,
+                    int64_t *target);
+
+void sam_corpus_free(sam_corpus *corpus);
+
+/*
+ * Create a batch of `batch` sequences and ingest their prompts: every prompt
+ * token goes through the static Transfer and the dynamic Transfer + Expand
+ * (Section 3.3 applied to the prompt; Section 3.1 builds the dynamic automaton
+ * over prompt and generated tokens alike).
+ *   corpus         : from sam_build, or NULL for dynamic-only operation.
+ *   prompt_tokens  : device, int32, all prompts concatenated.
+ *   prompt_offsets : device, int64 [batch+1], prompt b is
+ *                    prompt_tokens[offsets[b] : offsets[b+1]); non-decreasing.
+ *   vocab          : token range when corpus is NULL; ignored (the corpus's
+ *                    vocabulary is used) otherwise.
+ *   max_seq_len    : capacity of every sequence (prompt + generated tokens),
+ *                    1 .. 2^30.  Device memory is reserved for the worst case
+ *                    of 2*max_seq_len states and 3*max_seq_len transitions.
+ *   max_accept     : row length of `accepted` in sam_batch_step, 1 .. 4096.
+ *   draft_len      : draft tokens per sequence, 1 .. 1024.
+ *   l_bias         : the static source is chosen only if l1 > l2 + l_bias.
+ * Synchronises (it reads the offsets back to validate them).  Errors:
+ * SAM_EINVAL, SAM_ECAPACITY (a prompt longer than max_seq_len), SAM_ETOKEN
+ * (reported after the ingest kernel ran), SAM_ENOMEM, SAM_EDEVICE.
+ */
+int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
+                   const int64_t *prompt_offsets, int32_t batch, int32_t vocab,
+                   int32_t max_seq_len, int32_t max_accept, int32_t draft_len,
+                   int32_t l_bias, void *hip_stream, sam_batch **out);
+
+/*
+ * One generation round for the whole batch, one kernel launch.  For sequence b
+ * the first counts[b] tokens of row b of `accepted` are fed in order: static
+ * Transfer per token (Algorithm 1), dynamic match on the automaton as it stands
+ * and then Expand (Section 3.3, Algorithm 2).  Then the source is selected and
+ * the draft read.
+ *   accepted  : device, int32 [batch, max_accept].
+ *   counts    : device, int32 [batch], each 0 .. max_accept.  0 leaves the
+ *               sequence untouched and re-emits its current draft.
+ *   match_len : device, int32 [batch]; length of the chosen match.
+ *   draft     : device, int32 [batch, draft_len]; padded with -1.
+ *   draft_len : device, int32 [batch]; tokens before the padding.  The draft
+ *               is cut at the end of the source text.
+ *   source    : device, int32 [batch]; SAM_SOURCE_*.
+ * Asynchronous.  Device-side faults (capacity, bad token, bad count) never
+ * touch another sequence; they set bits readable with sam_batch_status.
+ * Errors: SAM_EINVAL, SAM_EDEVICE (launch failure).
+ */
+int sam_batch_step(sam_batch *batch, const int32_t *accepted, const int32_t *counts,
+                   int32_t *match_len, int32_t *draft, int32_t *draft_len,
+                   int32_t *source, void *hip_stream);
+
+/*
+ * Both cursors of every sequence, for checking: static (s1, l1) and dynamic
+ * (s2, l2), each device int32 [batch]; any may be NULL.  The dynamic cursor is
+ * the state holding the longest suffix of the sequence that also ends earlier
+ * in it.  Asynchronous.
+ */
+int sam_batch_debug(const sam_batch *batch, int32_t *s1, int32_t *l1, int32_t *s2,
+                    int32_t *l2, void *hip_stream);
+
+/*
+ * Per-sequence sizes of the dynamic automata: text length, states and
+ * transitions, each device int32 [batch]; any may be NULL.  Asynchronous.
+ */
+int sam_batch_sizes(const sam_batch *batch, int32_t *text_len, int32_t *n_states,
+                    int32_t *n_trans, void *hip_stream);
+
+/* OR of the SAM_STATUS_* bits raised so far.  Synchronises the stream. */
+int sam_batch_status(const sam_batch *batch, uint32_t *status, void *hip_stream);
+
+/* Bytes of device memory the batch holds. */
+int sam_batch_info(const sam_batch *batch, int64_t *device_bytes);
+
+void sam_batch_free(sam_batch *batch);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAM_H_ */

@@ -1,0 +1,220 @@
+"""ctypes binding over the C ABI declared in ``include/sam.h``.
+
+Argument marshalling only: every step of the path runs in the HIP library.  The
+functions carry the names of the C entry points.  Device buffers are torch
+tensors (PyTorch is used for device memory and streams and nothing else); their
+``data_ptr()`` is what crosses the boundary.  If the compiled library is missing
+the import of this module fails loudly; there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+SAM_OK, SAM_EINVAL, SAM_ENOMEM, SAM_ECAPACITY, SAM_ETOKEN, SAM_EDEVICE = 0, -1, -2, -3, -4, -5
+SAM_STATUS_CAPACITY, SAM_STATUS_TOKEN, SAM_STATUS_COUNT, SAM_STATUS_INTERNAL = 1, 2, 4, 8
+SAM_SOURCE_NONE, SAM_SOURCE_DYNAMIC, SAM_SOURCE_STATIC = 0, 1, 2
+
+EXPORTS = [
+    "sam_last_error", "sam_build", "sam_build_host_only", "sam_corpus_info",
+    "sam_corpus_export", "sam_corpus_find", "sam_corpus_free", "sam_batch_init",
+    "sam_batch_step", "sam_batch_debug", "sam_batch_sizes", "sam_batch_status",
+    "sam_batch_info", "sam_batch_free",
+]
+
+
+class SamError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("sam error %d: %s" % (code, msg))
+        self.code = code
+
+
+def _load():
+    path = _build.LIB
+    if not os.path.exists(path):
+        # nothing built yet: build once; a stale library is the caller's business
+        _build.build()
+    L = C.CDLL(path)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    L.sam_last_error.restype = C.c_char_p
+    L.sam_build.argtypes = [vp, i64, i32, C.POINTER(vp)]
+    L.sam_build_host_only.argtypes = [vp, i64, i32, C.POINTER(vp)]
+    L.sam_corpus_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+    L.sam_corpus_export.argtypes = [vp, vp, vp, vp]
+    L.sam_corpus_find.argtypes = [vp, i64, i32, C.POINTER(i64)]
+    L.sam_corpus_free.argtypes = [vp]
+    L.sam_corpus_free.restype = None
+    L.sam_batch_init.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, C.POINTER(vp)]
+    L.sam_batch_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+    L.sam_batch_debug.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.sam_batch_sizes.argtypes = [vp, vp, vp, vp, vp]
+    L.sam_batch_status.argtypes = [vp, C.POINTER(C.c_uint32), vp]
+    L.sam_batch_info.argtypes = [vp, C.POINTER(i64)]
+    L.sam_batch_free.argtypes = [vp]
+    L.sam_batch_free.restype = None
+    for name in EXPORTS:
+        if name not in ("sam_last_error", "sam_corpus_free", "sam_batch_free"):
+            getattr(L, name).restype = C.c_int
+    return L
+
+
+_lib = _load()
+LIB_PATH = _build.LIB
+
+
+def _check(rc: int):
+    if rc != SAM_OK:
+        raise SamError(rc, _lib.sam_last_error().decode("utf-8", "replace"))
+
+
+def _dev_ptr(t, dtype, what):
+    """Pointer of a contiguous device tensor of the given torch dtype (None -> NULL)."""
+    if t is None:
+        return None
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a device tensor" % what)
+    if t.dtype != dtype or not t.is_contiguous():
+        raise TypeError("%s must be contiguous %s" % (what, dtype))
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def sam_last_error() -> str:
+    return _lib.sam_last_error().decode("utf-8", "replace")
+
+
+class Corpus:
+    """Owner of a ``sam_corpus*``."""
+
+    def __init__(self, handle):
+        self._h = handle
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h:
+            _lib.sam_corpus_free(h)
+
+
+class Batch:
+    """Owner of a ``sam_batch*``; keeps the corpus alive."""
+
+    def __init__(self, handle, corpus, batch, max_accept, draft_len):
+        self._h = handle
+        self._corpus = corpus
+        self.batch, self.max_accept, self.draft_len = batch, max_accept, draft_len
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h:
+            _lib.sam_batch_free(h)
+
+
+def _host_tokens(tokens):
+    a = np.ascontiguousarray(tokens, dtype=np.int32)
+    return a, a.ctypes.data_as(C.c_void_p)
+
+
+def sam_build(corpus_tokens, vocab: int) -> Corpus:
+    a, p = _host_tokens(corpus_tokens)
+    h = C.c_void_p()
+    _check(_lib.sam_build(p, a.size, vocab, C.byref(h)))
+    return Corpus(h)
+
+
+def sam_build_host_only(corpus_tokens, vocab: int) -> Corpus:
+    a, p = _host_tokens(corpus_tokens)
+    h = C.c_void_p()
+    _check(_lib.sam_build_host_only(p, a.size, vocab, C.byref(h)))
+    return Corpus(h)
+
+
+def sam_corpus_info(corpus: Corpus):
+    """-> (n_states, n_trans, device_bytes)."""
+    a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(_lib.sam_corpus_info(corpus._h, C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
+
+
+def sam_corpus_export(corpus: Corpus):
+    """-> (length, link, min_endpos) host int32 arrays [n_states]."""
+    n = sam_corpus_info(corpus)[0]
+    out = [np.empty(n, dtype=np.int32) for _ in range(3)]
+    _check(_lib.sam_corpus_export(corpus._h, *[x.ctypes.data_as(C.c_void_p) for x in out]))
+    return tuple(out)
+
+
+def sam_corpus_find(corpus: Corpus, state: int, token: int) -> int:
+    t = C.c_int64()
+    _check(_lib.sam_corpus_find(corpus._h, state, token, C.byref(t)))
+    return t.value
+
+
+def sam_batch_init(corpus, prompt_tokens, prompt_offsets, batch: int, vocab: int,
+                   max_seq_len: int, max_accept: int, draft_len: int, l_bias: int = 0,
+                   stream=None) -> Batch:
+    import torch
+    h = C.c_void_p()
+    _check(_lib.sam_batch_init(corpus._h if corpus is not None else None,
+                               _dev_ptr(prompt_tokens, torch.int32, "prompt_tokens"),
+                               _dev_ptr(prompt_offsets, torch.int64, "prompt_offsets"),
+                               batch, vocab, max_seq_len, max_accept, draft_len, l_bias,
+                               _stream_ptr(stream), C.byref(h)))
+    return Batch(h, corpus, batch, max_accept, draft_len)
+
+
+def sam_batch_step(batch: Batch, accepted, counts, match_len, draft, draft_len, source,
+                   stream=None) -> None:
+    import torch
+    i32 = torch.int32
+    if accepted is not None and accepted.numel() != batch.batch * batch.max_accept:
+        raise ValueError("accepted must hold batch * max_accept tokens")
+    if draft is not None and draft.numel() != batch.batch * batch.draft_len:
+        raise ValueError("draft must hold batch * draft_len tokens")
+    for name, t in (("counts", counts), ("match_len", match_len), ("draft_len", draft_len),
+                    ("source", source)):
+        if t is not None and t.numel() != batch.batch:
+            raise ValueError("%s must hold batch values" % name)
+    _check(_lib.sam_batch_step(batch._h, _dev_ptr(accepted, i32, "accepted"),
+                               _dev_ptr(counts, i32, "counts"),
+                               _dev_ptr(match_len, i32, "match_len"),
+                               _dev_ptr(draft, i32, "draft"),
+                               _dev_ptr(draft_len, i32, "draft_len"),
+                               _dev_ptr(source, i32, "source"), _stream_ptr(stream)))
+
+
+def sam_batch_debug(batch: Batch, s1, l1, s2, l2, stream=None) -> None:
+    import torch
+    i32 = torch.int32
+    _check(_lib.sam_batch_debug(batch._h, _dev_ptr(s1, i32, "s1"), _dev_ptr(l1, i32, "l1"),
+                                _dev_ptr(s2, i32, "s2"), _dev_ptr(l2, i32, "l2"),
+                                _stream_ptr(stream)))
+
+
+def sam_batch_sizes(batch: Batch, text_len, n_states, n_trans, stream=None) -> None:
+    import torch
+    i32 = torch.int32
+    _check(_lib.sam_batch_sizes(batch._h, _dev_ptr(text_len, i32, "text_len"),
+                                _dev_ptr(n_states, i32, "n_states"),
+                                _dev_ptr(n_trans, i32, "n_trans"), _stream_ptr(stream)))
+
+
+def sam_batch_status(batch: Batch, stream=None) -> int:
+    st = C.c_uint32()
+    _check(_lib.sam_batch_status(batch._h, C.byref(st), _stream_ptr(stream)))
+    return st.value
+
+
+def sam_batch_info(batch: Batch) -> int:
+    b = C.c_int64()
+    _check(_lib.sam_batch_info(batch._h, C.byref(b)))
+    return b.value

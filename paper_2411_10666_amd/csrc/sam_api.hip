@@ -1,0 +1,344 @@
+// C ABI of the library (see include/sam.h): argument checks, device memory and
+// kernel launches.  All arithmetic of the method runs in the kernels
+// (sam_kernels.hip) and, for the corpus automaton, in the host builder
+// (sam_host.cpp).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/sam.h"
+#include "sam_device.h"
+#include "sam_host.h"
+
+using namespace sam;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const std::string &msg)
+{
+    g_err = msg;
+    return code;
+}
+
+int fail_hip(const char *what, hipError_t e)
+{
+    g_err = std::string(what) + ": " + hipGetErrorString(e);
+    return e == hipErrorOutOfMemory ? SAM_ENOMEM : SAM_EDEVICE;
+}
+
+#define HIP_TRY(expr)                                      \
+    do {                                                   \
+        hipError_t e_ = (expr);                            \
+        if (e_ != hipSuccess) return fail_hip(#expr, e_);  \
+    } while (0)
+
+}  // namespace
+
+struct sam_corpus {
+    HostSam    host;
+    bool       on_device = false;
+    int        device = -1;
+    StaticView view = {};
+    void      *d_text = nullptr, *d_linkrec = nullptr, *d_root = nullptr, *d_slots = nullptr;
+    int64_t    device_bytes = 0;
+};
+
+struct sam_batch {
+    const sam_corpus *corpus = nullptr;
+    BatchView         view = {};
+    int64_t           device_bytes = 0;
+};
+
+extern "C" {
+
+const char *sam_last_error(void) { return g_err.c_str(); }
+
+static void corpus_release_device(sam_corpus *c)
+{
+    if (c->d_text) (void)hipFree(c->d_text);
+    if (c->d_linkrec) (void)hipFree(c->d_linkrec);
+    if (c->d_root) (void)hipFree(c->d_root);
+    if (c->d_slots) (void)hipFree(c->d_slots);
+    c->d_text = c->d_linkrec = c->d_root = c->d_slots = nullptr;
+}
+
+static int corpus_upload(sam_corpus *c)
+{
+    const HostSam &h = c->host;
+    std::vector<LinkRec> lr;
+    try {
+        h.make_linkrec(lr);
+    } catch (const std::bad_alloc &) {
+        return fail(SAM_ENOMEM, "sam_build: out of host memory for the link records");
+    }
+    const size_t b_text = (size_t)h.n_tokens * sizeof(int32_t);
+    const size_t b_lr = (size_t)h.n_states * sizeof(LinkRec);
+    const size_t b_root = (size_t)h.vocab * sizeof(RootEnt);
+    const size_t b_slots = (size_t)h.n_buckets * kBucketSlots * sizeof(Slot);
+    HIP_TRY(hipGetDevice(&c->device));
+    HIP_TRY(hipMalloc(&c->d_text, b_text));
+    HIP_TRY(hipMalloc(&c->d_linkrec, b_lr));
+    HIP_TRY(hipMalloc(&c->d_root, b_root));
+    HIP_TRY(hipMalloc(&c->d_slots, b_slots));
+    HIP_TRY(hipMemcpy(c->d_text, h.text.data(), b_text, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(c->d_linkrec, lr.data(), b_lr, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(c->d_root, h.root.data(), b_root, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(c->d_slots, h.slots, b_slots, hipMemcpyHostToDevice));
+    c->view.text = (const int32_t *)c->d_text;
+    c->view.linkrec = (const LinkRec *)c->d_linkrec;
+    c->view.root = (const RootEnt *)c->d_root;
+    c->view.slots = (const Slot *)c->d_slots;
+    c->view.n_buckets = h.n_buckets;
+    c->view.n_tokens = (uint32_t)h.n_tokens;
+    c->view.n_states = h.n_states;
+    c->device_bytes = (int64_t)(b_text + b_lr + b_root + b_slots);
+    c->on_device = true;
+    return SAM_OK;
+}
+
+static int build_common(const int32_t *tokens, int64_t n, int32_t vocab, bool upload,
+                        sam_corpus **out)
+{
+    if (!out) return fail(SAM_EINVAL, "sam_build: out is NULL");
+    *out = nullptr;
+    sam_corpus *c = new (std::nothrow) sam_corpus;
+    if (!c) return fail(SAM_ENOMEM, "sam_build: out of host memory");
+    std::string err;
+    int rc;
+    try {
+        rc = c->host.build(tokens, n, vocab, err);
+    } catch (const std::bad_alloc &) {
+        rc = SAM_ENOMEM;
+        err = "sam_build: out of host memory";
+    }
+    if (rc != SAM_OK) {
+        delete c;
+        return fail(rc, err);
+    }
+    if (upload) {
+        rc = corpus_upload(c);
+        if (rc != SAM_OK) {
+            corpus_release_device(c);
+            delete c;
+            return rc;
+        }
+    }
+    *out = c;
+    return SAM_OK;
+}
+
+int sam_build(const int32_t *corpus_tokens, int64_t n_tokens, int32_t vocab, sam_corpus **out)
+{
+    return build_common(corpus_tokens, n_tokens, vocab, true, out);
+}
+
+int sam_build_host_only(const int32_t *corpus_tokens, int64_t n_tokens, int32_t vocab,
+                        sam_corpus **out)
+{
+    return build_common(corpus_tokens, n_tokens, vocab, false, out);
+}
+
+int sam_corpus_info(const sam_corpus *c, int64_t *n_states, int64_t *n_trans,
+                    int64_t *device_bytes)
+{
+    if (!c) return fail(SAM_EINVAL, "sam_corpus_info: corpus is NULL");
+    if (n_states) *n_states = c->host.n_states;
+    if (n_trans) *n_trans = (int64_t)c->host.n_trans;
+    if (device_bytes) *device_bytes = c->device_bytes;
+    return SAM_OK;
+}
+
+int sam_corpus_export(const sam_corpus *c, int32_t *length, int32_t *link, int32_t *min_endpos)
+{
+    if (!c) return fail(SAM_EINVAL, "sam_corpus_export: corpus is NULL");
+    const HostSam &h = c->host;
+    for (uint32_t s = 0; s < h.n_states; s++) {
+        if (length) length[s] = (int32_t)h.len[s];
+        if (link) link[s] = h.link[s] == kNil ? -1 : (int32_t)h.link[s];
+        if (min_endpos) min_endpos[s] = (int32_t)h.endpos[s];
+    }
+    return SAM_OK;
+}
+
+int sam_corpus_find(const sam_corpus *c, int64_t state, int32_t token, int64_t *target)
+{
+    if (!c || !target) return fail(SAM_EINVAL, "sam_corpus_find: NULL argument");
+    if (state < 0 || state >= (int64_t)c->host.n_states || token < 0 || token >= c->host.vocab)
+        return fail(SAM_EINVAL, "sam_corpus_find: state or token out of range");
+    const uint32_t d = c->host.find((uint32_t)state, (uint32_t)token);
+    *target = d == kNil ? -1 : (int64_t)d;
+    return SAM_OK;
+}
+
+void sam_corpus_free(sam_corpus *c)
+{
+    if (!c) return;
+    corpus_release_device(c);
+    delete c;
+}
+
+static void batch_release(sam_batch *b)
+{
+    if (b->view.dyn_text) (void)hipFree(b->view.dyn_text);
+    if (b->view.dyn_rec) (void)hipFree(b->view.dyn_rec);
+    if (b->view.dyn_slots) (void)hipFree(b->view.dyn_slots);
+    if (b->view.meta) (void)hipFree(b->view.meta);
+    if (b->view.status) (void)hipFree(b->view.status);
+    delete b;
+}
+
+int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
+                   const int64_t *prompt_offsets, int32_t batch, int32_t vocab,
+                   int32_t max_seq_len, int32_t max_accept, int32_t draft_len, int32_t l_bias,
+                   void *hip_stream, sam_batch **out)
+{
+    if (!out) return fail(SAM_EINVAL, "sam_batch_init: out is NULL");
+    *out = nullptr;
+    if (!prompt_tokens || !prompt_offsets)
+        return fail(SAM_EINVAL, "sam_batch_init: prompt_tokens / prompt_offsets is NULL");
+    if (batch < 1) return fail(SAM_EINVAL, "sam_batch_init: batch must be >= 1");
+    if (max_seq_len < 1 || max_seq_len > (1 << 30))
+        return fail(SAM_EINVAL, "sam_batch_init: max_seq_len must be in 1 .. 2^30");
+    if (max_accept < 1 || max_accept > 4096)
+        return fail(SAM_EINVAL, "sam_batch_init: max_accept must be in 1 .. 4096");
+    if (draft_len < 1 || draft_len > 1024)
+        return fail(SAM_EINVAL, "sam_batch_init: draft_len must be in 1 .. 1024");
+    if (corpus && !corpus->on_device)
+        return fail(SAM_EINVAL, "sam_batch_init: corpus was built host-only");
+    if (corpus) vocab = corpus->host.vocab;
+    if (vocab < 1) return fail(SAM_EINVAL, "sam_batch_init: vocab must be >= 1");
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    // the offsets decide how far each wave reads: check them before any launch
+    std::vector<int64_t> offs;
+    try {
+        offs.resize((size_t)batch + 1);
+    } catch (const std::bad_alloc &) {
+        return fail(SAM_ENOMEM, "sam_batch_init: out of host memory");
+    }
+    HIP_TRY(hipMemcpyAsync(offs.data(), prompt_offsets, offs.size() * sizeof(int64_t),
+                           hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    if (offs[0] < 0) return fail(SAM_EINVAL, "sam_batch_init: prompt_offsets[0] < 0");
+    for (int32_t b = 0; b < batch; b++) {
+        const int64_t len = offs[b + 1] - offs[b];
+        if (len < 0) return fail(SAM_EINVAL, "sam_batch_init: prompt_offsets must not decrease");
+        if (len > max_seq_len)
+            return fail(SAM_ECAPACITY, "sam_batch_init: prompt " + std::to_string(b) + " has " +
+                                           std::to_string(len) + " tokens, max_seq_len is " +
+                                           std::to_string(max_seq_len));
+    }
+
+    sam_batch *bt = new (std::nothrow) sam_batch;
+    if (!bt) return fail(SAM_ENOMEM, "sam_batch_init: out of host memory");
+    bt->corpus = corpus;
+    BatchView &v = bt->view;
+    v.batch = batch;
+    v.vocab = vocab;
+    v.max_seq_len = (uint32_t)max_seq_len;
+    v.max_states = 2u * (uint32_t)max_seq_len + 2u;
+    v.dyn_buckets = (uint32_t)dynamic_buckets_for(max_seq_len);
+    v.max_accept = max_accept;
+    v.draft_len = draft_len;
+    v.l_bias = l_bias;
+    v.has_static = corpus ? 1 : 0;
+    const size_t b_text = (size_t)batch * max_seq_len * sizeof(int32_t);
+    const size_t b_rec = (size_t)batch * v.max_states * sizeof(DynRec);
+    const size_t b_slots = (size_t)batch * v.dyn_buckets * kBucketSlots * sizeof(Slot);
+    const size_t b_meta = (size_t)batch * sizeof(SeqMeta);
+    hipError_t e;
+    if ((e = hipMalloc((void **)&v.dyn_text, b_text)) != hipSuccess ||
+        (e = hipMalloc((void **)&v.dyn_rec, b_rec)) != hipSuccess ||
+        (e = hipMalloc((void **)&v.dyn_slots, b_slots)) != hipSuccess ||
+        (e = hipMalloc((void **)&v.meta, b_meta)) != hipSuccess ||
+        (e = hipMalloc((void **)&v.status, 256)) != hipSuccess) {
+        batch_release(bt);
+        return fail_hip("sam_batch_init: hipMalloc", e);
+    }
+    bt->device_bytes = (int64_t)(b_text + b_rec + b_slots + b_meta + 256);
+    StaticView S = corpus ? corpus->view : StaticView{};
+    if ((e = hipMemsetAsync(v.dyn_slots, 0xFF, b_slots, stream)) != hipSuccess ||
+        (e = launch_reset(v, stream)) != hipSuccess ||
+        (e = launch_feed(S, v, prompt_tokens, prompt_offsets, nullptr, nullptr, nullptr, nullptr,
+                         nullptr, stream)) != hipSuccess ||
+        (e = hipStreamSynchronize(stream)) != hipSuccess) {
+        batch_release(bt);
+        return fail_hip("sam_batch_init: prompt ingest", e);
+    }
+    uint32_t st = 0;
+    if ((e = hipMemcpy(&st, v.status, sizeof(st), hipMemcpyDeviceToHost)) != hipSuccess) {
+        batch_release(bt);
+        return fail_hip("sam_batch_init: status read", e);
+    }
+    if (st & SAM_STATUS_TOKEN) {
+        batch_release(bt);
+        return fail(SAM_ETOKEN, "sam_batch_init: a prompt token is outside [0, vocab)");
+    }
+    *out = bt;
+    return SAM_OK;
+}
+
+int sam_batch_step(sam_batch *bt, const int32_t *accepted, const int32_t *counts,
+                   int32_t *match_len, int32_t *draft, int32_t *draft_len, int32_t *source,
+                   void *hip_stream)
+{
+    if (!bt) return fail(SAM_EINVAL, "sam_batch_step: batch is NULL");
+    if (!accepted || !counts || !match_len || !draft || !draft_len || !source)
+        return fail(SAM_EINVAL, "sam_batch_step: NULL buffer");
+    StaticView S = bt->corpus ? bt->corpus->view : StaticView{};
+    hipError_t e = launch_feed(S, bt->view, accepted, nullptr, counts, match_len, draft,
+                               draft_len, source, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail_hip("sam_batch_step: launch", e);
+    return SAM_OK;
+}
+
+int sam_batch_debug(const sam_batch *bt, int32_t *s1, int32_t *l1, int32_t *s2, int32_t *l2,
+                    void *hip_stream)
+{
+    if (!bt) return fail(SAM_EINVAL, "sam_batch_debug: batch is NULL");
+    hipError_t e = launch_debug(bt->view, s1, l1, s2, l2, nullptr, nullptr, nullptr,
+                                (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail_hip("sam_batch_debug: launch", e);
+    return SAM_OK;
+}
+
+int sam_batch_sizes(const sam_batch *bt, int32_t *text_len, int32_t *n_states, int32_t *n_trans,
+                    void *hip_stream)
+{
+    if (!bt) return fail(SAM_EINVAL, "sam_batch_sizes: batch is NULL");
+    hipError_t e = launch_debug(bt->view, nullptr, nullptr, nullptr, nullptr, text_len, n_states,
+                                n_trans, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail_hip("sam_batch_sizes: launch", e);
+    return SAM_OK;
+}
+
+int sam_batch_status(const sam_batch *bt, uint32_t *status, void *hip_stream)
+{
+    if (!bt || !status) return fail(SAM_EINVAL, "sam_batch_status: NULL argument");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    HIP_TRY(hipMemcpyAsync(status, bt->view.status, sizeof(uint32_t), hipMemcpyDeviceToHost,
+                           stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    return SAM_OK;
+}
+
+int sam_batch_info(const sam_batch *bt, int64_t *device_bytes)
+{
+    if (!bt || !device_bytes) return fail(SAM_EINVAL, "sam_batch_info: NULL argument");
+    *device_bytes = bt->device_bytes;
+    return SAM_OK;
+}
+
+void sam_batch_free(sam_batch *bt)
+{
+    if (!bt) return;
+    batch_release(bt);
+}
+
+}  // extern "C"

@@ -1,0 +1,52 @@
+// Kernel argument blocks and launcher prototypes (device side of the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sam_layout.h"
+
+namespace sam {
+
+constexpr uint32_t SAM_STATUS_CAPACITY_BIT = 1u;
+constexpr uint32_t SAM_STATUS_TOKEN_BIT    = 2u;
+constexpr uint32_t SAM_STATUS_COUNT_BIT    = 4u;
+constexpr uint32_t SAM_STATUS_INTERNAL_BIT = 8u;
+
+// Static automaton in device memory (all read-only for the kernels).
+struct StaticView {
+    const int32_t *text;
+    const LinkRec *linkrec;
+    const RootEnt *root;
+    const Slot    *slots;
+    uint64_t       n_buckets;
+    uint32_t       n_tokens;
+    uint32_t       n_states;
+};
+
+// A batch of sequences: per-sequence regions are laid out back to back.
+struct BatchView {
+    int32_t   batch;
+    int32_t   vocab;
+    uint32_t  max_seq_len;
+    uint32_t  max_states;      // records per sequence (2 * max_seq_len + 2)
+    uint32_t  dyn_buckets;     // buckets per sequence
+    int32_t   max_accept;
+    int32_t   draft_len;
+    int32_t   l_bias;
+    int32_t   has_static;
+    int32_t  *dyn_text;        // [batch, max_seq_len]
+    DynRec   *dyn_rec;         // [batch, max_states]
+    Slot     *dyn_slots;       // [batch, dyn_buckets * 8]
+    SeqMeta  *meta;            // [batch]
+    uint32_t *status;          // [1]
+};
+
+hipError_t launch_feed(const StaticView &S, const BatchView &B, const int32_t *tokens,
+                       const int64_t *offsets, const int32_t *counts, int32_t *match_len,
+                       int32_t *draft, int32_t *draft_len, int32_t *source, hipStream_t stream);
+hipError_t launch_reset(const BatchView &B, hipStream_t stream);
+hipError_t launch_debug(const BatchView &B, int32_t *s1, int32_t *l1, int32_t *s2, int32_t *l2,
+                        int32_t *text_len, int32_t *n_states, int32_t *n_trans,
+                        hipStream_t stream);
+
+}  // namespace sam

@@ -1,0 +1,178 @@
+// Build-SAM on the host (Algorithm 2, Appendix A.1 of arxiv 2411.10666), written
+// straight into the device layout: state fields in flat arrays, the root's
+// transitions in a direct-indexed table, all other transitions in the bucketed
+// open-addressed hash.  While building, Slot::w chains each state's slots so a
+// clone can enumerate the transitions it copies; the last pass overwrites it
+// with min_endpos(target), which is what the device wants there.
+#include "sam_host.h"
+
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "../../include/sam.h"
+
+namespace sam {
+
+HostSam::~HostSam() { free(slots); }
+
+namespace {
+
+// Probe for (state, token).  Returns the slot index if present; otherwise kNil64
+// and *empty_at = first empty slot on the probe path (where an insert goes).
+constexpr uint64_t kNil64 = ~0ull;
+
+inline uint64_t probe(const Slot *slots, uint64_t n_buckets, uint32_t state, uint32_t token,
+                      uint64_t *empty_at)
+{
+    uint64_t b = bucket_of(hash_key(state, token), n_buckets);
+    for (;;) {
+        const Slot *s = slots + b * kBucketSlots;
+        for (int i = 0; i < kBucketSlots; i++) {
+            if (s[i].state == state && s[i].token == token) return b * kBucketSlots + i;
+            if (s[i].state == kNil) {
+                if (empty_at) *empty_at = b * kBucketSlots + i;
+                return kNil64;
+            }
+        }
+        if (++b == n_buckets) b = 0;
+    }
+}
+
+}  // namespace
+
+int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string &err)
+{
+    if (!tokens || n < 1 || n > 0x7FFFFFFELL || vocab_ < 1) {
+        err = "sam_build: need tokens != NULL, 1 <= n_tokens <= 2^31-2, vocab >= 1";
+        return SAM_EINVAL;
+    }
+    for (int64_t i = 0; i < n; i++)
+        if (tokens[i] < 0 || tokens[i] >= vocab_) {
+            err = "sam_build: corpus token " + std::to_string(tokens[i]) + " at position " +
+                  std::to_string(i) + " is outside [0, vocab)";
+            return SAM_ETOKEN;
+        }
+    n_tokens = n;
+    vocab = vocab_;
+    n_buckets = static_buckets_for(n);
+    const uint64_t n_slots = n_buckets * kBucketSlots;
+    if (n_slots >= 0xFFFFFFFFull) {
+        err = "sam_build: corpus too large for 32-bit slot indices";
+        return SAM_EINVAL;
+    }
+    try {
+        text.assign(tokens, tokens + n);
+        const size_t cap = (size_t)2 * n + 2;
+        len.reserve(cap);
+        link.reserve(cap);
+        endpos.reserve(cap);
+        head.reserve(cap);
+        root.assign((size_t)vocab, RootEnt{0, 0});
+    } catch (const std::bad_alloc &) {
+        err = "sam_build: out of host memory for the state arrays";
+        return SAM_ENOMEM;
+    }
+    slots = (Slot *)aligned_alloc(128, n_slots * sizeof(Slot));
+    if (!slots) {
+        err = "sam_build: out of host memory for the transition table";
+        return SAM_ENOMEM;
+    }
+    memset(slots, 0xFF, n_slots * sizeof(Slot));
+
+    auto new_state = [&](uint32_t l, uint32_t lk, uint32_t ep) -> uint32_t {
+        len.push_back(l);
+        link.push_back(lk);
+        endpos.push_back(ep);
+        head.push_back(kNil);
+        return n_states++;
+    };
+    auto put = [&](uint64_t at, uint32_t state, uint32_t token, uint32_t dst) {
+        slots[at] = Slot{state, token, dst, head[state]};
+        head[state] = (uint32_t)at;
+        n_trans++;
+    };
+
+    new_state(0, kNil, 0);     // root
+    uint32_t last = 0;
+
+    for (int64_t i = 0; i < n; i++) {
+        const uint32_t t = (uint32_t)tokens[i];
+        const uint32_t c = new_state((uint32_t)(i + 1), 0, (uint32_t)(i + 1));
+        uint32_t p = last;
+        uint32_t q = kNil;
+        uint64_t at = kNil64;          // slot of (p, t) when p is not the root
+        // give t-transitions to the states on last's suffix path that lack one
+        while (p != kNil) {
+            if (p == 0) {
+                if (root[t].dst) { q = root[t].dst; break; }
+                root[t].dst = c;
+                n_trans++;
+                p = kNil;
+            } else {
+                uint64_t empty_at = 0;
+                at = probe(slots, n_buckets, p, t, &empty_at);
+                if (at != kNil64) { q = slots[at].dst; break; }
+                put(empty_at, p, t, c);
+                p = link[p];
+            }
+        }
+        if (p == kNil) {
+            link[c] = 0;
+        } else if (len[p] + 1 == len[q]) {
+            link[c] = q;
+        } else {
+            const uint32_t cl = new_state(len[p] + 1, link[q], endpos[q]);
+            for (uint32_t j = head[q]; j != kNil; j = slots[j].w) {
+                uint64_t empty_at = 0;
+                probe(slots, n_buckets, cl, slots[j].token, &empty_at);
+                put(empty_at, cl, slots[j].token, slots[j].dst);
+            }
+            // states further up the path that still point at q now point at the clone
+            while (p != kNil) {
+                if (p == 0) {
+                    if (root[t].dst != q) break;
+                    root[t].dst = cl;
+                    p = kNil;
+                } else {
+                    if (at == kNil64) at = probe(slots, n_buckets, p, t, nullptr);
+                    if (at == kNil64 || slots[at].dst != q) break;
+                    slots[at].dst = cl;
+                    p = link[p];
+                    at = kNil64;
+                }
+            }
+            link[q] = cl;
+            link[c] = cl;
+        }
+        last = c;
+    }
+
+    // the device reads min_endpos(target) where the build kept the list chain
+    for (uint64_t j = 0; j < n_slots; j++)
+        if (slots[j].state != kNil) slots[j].w = endpos[slots[j].dst];
+    for (int32_t t = 0; t < vocab; t++)
+        if (root[t].dst) root[t].endpos = endpos[root[t].dst];
+    std::vector<uint32_t>().swap(head);
+    return SAM_OK;
+}
+
+uint32_t HostSam::find(uint32_t state, uint32_t token) const
+{
+    if (state >= n_states || token >= (uint32_t)vocab) return kNil;
+    if (state == 0) return root[token].dst ? root[token].dst : kNil;
+    uint64_t at = probe(slots, n_buckets, state, token, nullptr);
+    return at == kNil64 ? kNil : slots[at].dst;
+}
+
+void HostSam::make_linkrec(std::vector<LinkRec> &out) const
+{
+    out.resize(n_states);
+    out[0] = LinkRec{0, 0};
+    for (uint32_t s = 1; s < n_states; s++) out[s] = LinkRec{link[s], len[link[s]]};
+}
+
+void HostSam::release_build_only() { std::vector<uint32_t>().swap(head); }
+
+}  // namespace sam

@@ -1,0 +1,42 @@
+// Host-side construction of the static suffix automaton (Build-SAM, Algorithm 2
+// of arxiv 2411.10666) directly into the flat arrays the device kernels read.
+#pragma once
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "sam_layout.h"
+
+namespace sam {
+
+struct HostSam {
+    int64_t  n_tokens = 0;
+    int32_t  vocab = 0;
+    uint32_t n_states = 0;
+    uint64_t n_trans = 0;        // all transitions, the root's included
+    uint64_t n_buckets = 0;
+
+    std::vector<int32_t>  text;
+    std::vector<uint32_t> len, link, endpos;
+    std::vector<uint32_t> head;  // newest slot of each state's transition list (build only)
+    std::vector<RootEnt>  root;  // direct-indexed transitions of the root
+    Slot *slots = nullptr;       // n_buckets * 8, 128-byte aligned
+
+    ~HostSam();
+    HostSam() = default;
+    HostSam(const HostSam &) = delete;
+    HostSam &operator=(const HostSam &) = delete;
+
+    // returns SAM_OK or an error code; message in err
+    int build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string &err);
+
+    // next(state)[token] or kNil
+    uint32_t find(uint32_t state, uint32_t token) const;
+
+    // {link, length(link)} per state, for the device
+    void make_linkrec(std::vector<LinkRec> &out) const;
+
+    void release_build_only();   // drop arrays the device does not need
+};
+
+}  // namespace sam

@@ -1,0 +1,88 @@
+"""Host logic of the library without a GPU: the shared library loads and exports
+every declared symbol, argument checks, and the host-built corpus automaton
+against the CPU checker (states, links, end positions, every transition)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle.sam_oracle import Sam
+from paper_2411_10666_amd import binding as sam
+from paper_2411_10666_amd.synth import CONFIGS, make_corpus
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "sam.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(sam_[a-z_]+)\s*\(", hdr))
+    assert declared == set(sam.EXPORTS)
+    lib = ctypes.CDLL(sam.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def _compare(corpus_tokens, vocab):
+    c = sam.sam_build_host_only(corpus_tokens, vocab)
+    ref = Sam.build(corpus_tokens)
+    ns, nt, dev = sam.sam_corpus_info(c)
+    assert dev == 0
+    assert ns == ref.num_states and nt == ref.num_trans
+    length, link, endpos = sam.sam_corpus_export(c)
+    rlink, rlen, rend, _ = ref.states()
+    assert (length == rlen).all() and (link == rlink).all() and (endpos == rend).all()
+    return c, ref
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_host_build_matches_checker_small(seed):
+    rng = np.random.default_rng(seed)
+    vocab = [2, 3, 5, 50][seed % 4]
+    n = int(rng.integers(1, 400))
+    x = rng.integers(0, vocab, size=n).astype(np.int32)
+    c, ref = _compare(x, vocab)
+    src, tok, dst = ref.transitions()
+    for s, t, d in zip(src.tolist(), tok.tolist(), dst.tolist()):
+        assert sam.sam_corpus_find(c, s, t) == d
+    # transitions that do not exist are reported as such (counts already agree)
+    for s in range(min(ref.num_states, 50)):
+        have = set(tok[src == s].tolist())
+        for t in range(vocab):
+            if t not in have:
+                assert sam.sam_corpus_find(c, s, t) == -1
+
+
+def test_host_build_matches_checker_cfg1_corpus():
+    spec = CONFIGS["cfg1"]
+    x = make_corpus(spec)
+    c, ref = _compare(x, spec.vocab)
+    src, tok, dst = ref.transitions()
+    rng = np.random.default_rng(0)
+    pick = rng.choice(len(src), size=20000, replace=False)
+    for i in pick.tolist():
+        assert sam.sam_corpus_find(c, int(src[i]), int(tok[i])) == int(dst[i])
+
+
+def test_argument_errors():
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_build_host_only(np.zeros(0, dtype=np.int32), 10)
+    assert e.value.code == sam.SAM_EINVAL
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_build_host_only(np.array([1, 2, 10], dtype=np.int32), 10)
+    assert e.value.code == sam.SAM_ETOKEN and "position 2" in str(e.value)
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_build_host_only(np.array([1, -2], dtype=np.int32), 10)
+    assert e.value.code == sam.SAM_ETOKEN
+    c = sam.sam_build_host_only(np.array([1, 2, 3], dtype=np.int32), 10)
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_corpus_find(c, 99, 1)
+    assert e.value.code == sam.SAM_EINVAL
+    lib = ctypes.CDLL(sam.LIB_PATH)
+    assert lib.sam_corpus_info(None, None, None, None) == sam.SAM_EINVAL
+    assert lib.sam_batch_step(None, None, None, None, None, None, None, None) == sam.SAM_EINVAL
+    assert lib.sam_batch_status(None, None, None) == sam.SAM_EINVAL
+    lib.sam_corpus_free(None)
+    lib.sam_batch_free(None)

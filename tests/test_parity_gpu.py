@@ -1,0 +1,180 @@
+"""Parity of the HIP path with the CPU checker, element by element, through the
+C ABI.  Everything compared is an integer: match lengths, canonical state ids,
+sources, draft lengths, draft tokens and automaton sizes must be identical."""
+import numpy as np
+import pytest
+
+from parity_util import assert_same, run_gpu, run_oracle
+from paper_2411_10666_amd.synth import CONFIGS, make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[parity] " + msg, flush=True)
+
+
+def _random_case(seed, vocab, n_corpus, B, T, A, L, steps, ragged=True):
+    rng = np.random.default_rng(seed)
+    corpus = rng.integers(0, vocab, size=n_corpus).astype(np.int32) if n_corpus else None
+    prompts = []
+    for b in range(B):
+        pl = int(rng.integers(0, T // 3)) if ragged else T // 4
+        p = rng.integers(0, vocab, size=pl).astype(np.int32)
+        if corpus is not None and pl > 10:
+            j = int(rng.integers(0, n_corpus - 8))
+            p[2:10] = corpus[j:j + 8]
+        prompts.append(p)
+    used = np.array([len(p) for p in prompts])
+    counts = np.zeros((steps, B), dtype=np.int32)
+    acc = rng.integers(0, vocab, size=(steps, B, A)).astype(np.int32)
+    for s in range(steps):
+        c = rng.integers(0, A + 1, size=B)
+        c = np.minimum(c, T - used)
+        counts[s] = c
+        used += c
+        if corpus is not None:
+            for b in range(B):
+                if c[b] >= 3 and rng.random() < 0.5:
+                    j = int(rng.integers(0, n_corpus - c[b]))
+                    acc[s, b, :c[b]] = corpus[j:j + c[b]]
+    return corpus, prompts, acc, counts
+
+
+@pytest.mark.parametrize("seed,vocab", [(0, 2), (1, 3), (2, 4), (3, 7), (4, 40), (5, 32000)])
+def test_small_random_static_and_dynamic(seed, vocab):
+    B, T, A, L, steps = 13, 300, 6, 9, 40
+    _say("small random seed=%d vocab=%d B=%d T=%d" % (seed, vocab, B, T))
+    corpus, prompts, acc, counts = _random_case(seed, vocab, 2000, B, T, A, L, steps)
+    g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L, l_bias=seed % 3)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L, l_bias=seed % 3)
+    assert status == 0
+    assert_same(g, r)
+
+
+@pytest.mark.parametrize("seed,vocab", [(10, 2), (11, 3), (12, 30)])
+def test_dynamic_only(seed, vocab):
+    B, T, A, L, steps = 9, 500, 16, 32, 30
+    _say("dynamic only seed=%d vocab=%d" % (seed, vocab))
+    _, prompts, acc, counts = _random_case(seed, vocab, 0, B, T, A, L, steps)
+    g, status, _ = run_gpu(None, vocab, prompts, acc, counts, T, A, L)
+    r, _ = run_oracle(None, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r, has_static=False)
+
+
+def test_long_rows_and_wide_drafts():
+    """max_accept above one wavefront of tokens and draft_len above 64 lanes."""
+    B, T, A, L, steps, vocab = 5, 1500, 150, 200, 8, 3
+    _say("long rows A=%d L=%d" % (A, L))
+    corpus, prompts, acc, counts = _random_case(21, vocab, 3000, B, T, A, L, steps)
+    g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r)
+
+
+def test_single_token_sequences_fill_to_capacity():
+    """Sequences grown exactly to max_seq_len (the worst-case table sizes), one
+    repeated token and a two-token alternation included."""
+    vocab, T, A, L = 3, 256, 8, 4
+    prompts = [np.zeros(0, np.int32), np.zeros(5, np.int32), np.array([0, 1] * 10, np.int32)]
+    B = len(prompts)
+    rng = np.random.default_rng(3)
+    steps = T // 1
+    counts = np.zeros((steps, B), dtype=np.int32)
+    acc = np.zeros((steps, B, A), dtype=np.int32)
+    used = np.array([len(p) for p in prompts])
+    for s in range(steps):
+        c = np.minimum(rng.integers(1, A + 1, size=B), T - used)
+        counts[s] = c
+        used += c
+        acc[s, 2] = np.tile([0, 1], A // 2) if s % 2 == 0 else rng.integers(0, vocab, size=A)
+    assert (used == T).all()
+    _say("fill to capacity T=%d" % T)
+    corpus = rng.integers(0, vocab, size=500).astype(np.int32)
+    g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r)
+
+
+def test_cfg1_full():
+    spec = CONFIGS["cfg1"]
+    _say("cfg1 full workload")
+    w = make_workload(spec)
+    prompts = [w.prompts[b] for b in range(spec.batch)]
+    g, status, _ = run_gpu(w.corpus, spec.vocab, prompts, w.accepted, w.counts, spec.max_seq_len,
+                           spec.max_accept, spec.draft_len)
+    r, _ = run_oracle(w.corpus, prompts, w.accepted, w.counts, spec.max_accept, spec.draft_len)
+    assert status == 0
+    assert_same(g, r)
+    assert sum(int((x["source"] == 2).sum()) for x in r) > 0
+    assert sum(int((x["source"] == 1).sum()) for x in r) > 0
+
+
+def test_cfg4_scaled_dynamic_only():
+    spec = CONFIGS["cfg4"].scaled(batch=24, prompt_len=1500, gen_len=512)
+    _say("cfg4 scaled B=24 T=%d" % spec.max_seq_len)
+    w = make_workload(spec)
+    prompts = [w.prompts[b] for b in range(spec.batch)]
+    g, status, _ = run_gpu(None, spec.vocab, prompts, w.accepted, w.counts, spec.max_seq_len,
+                           spec.max_accept, spec.draft_len)
+    r, _ = run_oracle(None, prompts, w.accepted, w.counts, spec.max_accept, spec.draft_len)
+    assert status == 0
+    assert_same(g, r, has_static=False)
+
+
+def test_device_side_faults_leave_other_sequences_intact():
+    import torch
+    from paper_2411_10666_amd import binding as sam
+    vocab, T, A, L, B = 5, 46, 4, 3, 4
+    rng = np.random.default_rng(8)
+    corpus = rng.integers(0, vocab, size=200).astype(np.int32)
+    prompts = [rng.integers(0, vocab, size=16 if b == 2 else 10).astype(np.int32)
+               for b in range(B)]
+    steps = 12
+    acc = rng.integers(0, vocab, size=(steps, B, A)).astype(np.int32)
+    counts = np.full((steps, B), 3, dtype=np.int32)
+    # sequence 0: a bad token in step 2 (position 1); sequence 1: a bad count in
+    # step 3; sequence 2: runs out of room after step 9 (16 + 3*10 = 46);
+    # sequence 3: clean and ends exactly at capacity
+    acc_g = acc.copy(); cnt_g = counts.copy()
+    acc_g[2, 0, 1] = vocab + 3
+    cnt_g[3, 1] = A + 1
+    _say("device-side faults")
+    g, status, _ = run_gpu(corpus, vocab, prompts, acc_g, cnt_g, T, A, L)
+    assert status == (sam.SAM_STATUS_TOKEN | sam.SAM_STATUS_COUNT | sam.SAM_STATUS_CAPACITY)
+    # what the checker sees: the faulty part of each row is simply not fed
+    cnt_r = counts.copy()
+    cnt_r[2, 0] = 1
+    cnt_r[3, 1] = 0
+    cnt_r[10:, 2] = 0
+    r, _ = run_oracle(corpus, prompts, acc, cnt_r, A, L)
+    assert_same(g, r)
+
+
+def test_init_errors():
+    import torch
+    from paper_2411_10666_amd import binding as sam
+    dev = torch.device("cuda:0")
+    tok = torch.zeros(10, dtype=torch.int32, device=dev)
+    off = torch.tensor([0, 10], dtype=torch.int64, device=dev)
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_batch_init(None, tok, off, 1, 5, 8, 4, 4)
+    assert e.value.code == sam.SAM_ECAPACITY
+    bad = torch.tensor([5, 3], dtype=torch.int64, device=dev)
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_batch_init(None, tok, bad, 1, 5, 8, 4, 4)
+    assert e.value.code == sam.SAM_EINVAL
+    tok[4] = 77
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_batch_init(None, tok, off, 1, 5, 16, 4, 4)
+    assert e.value.code == sam.SAM_ETOKEN
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_batch_init(None, tok, off, 0, 5, 16, 4, 4)
+    assert e.value.code == sam.SAM_EINVAL
+    host_only = sam.sam_build_host_only(np.array([1, 2, 3], np.int32), 5)
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_batch_init(host_only, tok, off, 1, 5, 16, 4, 4)
+    assert e.value.code == sam.SAM_EINVAL
