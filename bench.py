@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched suffix-automaton draft path on one MI355X.
+
+A "step" is one ``sam_batch_step`` call over the whole batch: for every sequence
+the accepted tokens go through the static Transfer and the dynamic Expand, then
+source selection and the draft gather (one kernel launch).  The workload is a
+seeded synthetic one (``paper_2411_10666_amd.synth``); the corpus automaton is
+built and the prompts are ingested before the clock starts, and all inputs and
+outputs of the timed steps are already resident in device memory.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2]
+
+Prints one JSON line.  ``value`` is match-steps per second (one match-step = one
+accepted token of one sequence pushed through both automata).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2411_10666_amd.synth import CONFIGS, make_workload  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0
+
+# Algorithmic bytes one match-step moves, per workload: the operation counts of
+# the method (probes, suffix-link reads, inserts, redirects, clone copies, state
+# writes, text appends) and the draft gather, each priced at the element size of
+# the device layout.  Written by oracle/count_ops.py; derivation in the design doc.
+ALGO_BYTES_PER_MATCH_STEP = {
+    "cfg1": 214.0,
+    "cfg2": 214.0,
+    "cfg3": 214.0,
+    "cfg4": 214.0,
+    "cfg5": 214.0,
+}
+
+
+def _log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def gpu_leg(w, steps, warmup):
+    import torch
+    from paper_2411_10666_amd import binding as sam
+
+    spec = w.spec
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    t0 = time.time()
+    corpus = sam.sam_build(w.corpus, spec.vocab) if w.corpus is not None else None
+    build_s = time.time() - t0
+    info = sam.sam_corpus_info(corpus) if corpus is not None else (0, 0, 0)
+    _log("corpus automaton: %d states, %d transitions, %.1f MB on device, built in %.1f s"
+         % (info[0], info[1], info[2] / 1e6, build_s))
+
+    B, A, L = spec.batch, spec.max_accept, spec.draft_len
+    S = w.steps
+    d_prompts = torch.from_numpy(w.prompts.reshape(-1)).to(dev)
+    d_offs = torch.from_numpy(w.prompt_offsets).to(dev)
+    d_acc = torch.from_numpy(w.accepted).to(dev)
+    d_cnt = torch.from_numpy(w.counts).to(dev)
+    i32 = dict(dtype=torch.int32, device=dev)
+    ml = torch.zeros(S, B, **i32)
+    dl = torch.zeros(S, B, **i32)
+    src = torch.zeros(S, B, **i32)
+    dr = torch.zeros(S, B, L, **i32)
+    stream = torch.cuda.current_stream()
+
+    def new_batch():
+        torch.cuda.synchronize()
+        t = time.time()
+        b = sam.sam_batch_init(corpus, d_prompts, d_offs, B, spec.vocab, spec.max_seq_len, A, L,
+                               spec.l_bias, stream)
+        torch.cuda.synchronize()
+        dt = time.time() - t
+        b.plan = sam.StepPlan(b, d_acc, d_cnt, ml, dr, dl, src, stream)
+        return b, dt
+
+    def run(batch, lo, hi):
+        batch.plan.run(lo, hi)
+
+    # The schedule is replayed from its start as often as needed; each replay
+    # starts from freshly ingested prompts (untimed).
+    batch, init_s = new_batch()
+    pos = 0
+    left = warmup
+    while left > 0:
+        n = min(left, S - pos)
+        run(batch, pos, pos + n)
+        pos += n
+        left -= n
+        if pos == S:
+            batch, _ = new_batch()
+            pos = 0
+    torch.cuda.synchronize()
+
+    segs = []
+    timed_match_steps = 0
+    timed_draft_tokens = 0
+    wall = 0.0
+    left = steps
+    while left > 0:
+        if pos == S:
+            batch, _ = new_batch()
+            pos = 0
+        n = min(left, S - pos)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        e0.record(stream)
+        run(batch, pos, pos + n)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall += time.perf_counter() - t
+        segs.append((e0, e1))
+        timed_match_steps += int(w.counts[pos:pos + n].sum())
+        timed_draft_tokens += int(dl[pos:pos + n].sum().item())
+        pos += n
+        left -= n
+    ev_ms = sum(a.elapsed_time(b) for a, b in segs)
+    status = sam.sam_batch_status(batch)
+    if status != 0:
+        raise RuntimeError("device status word is %d after the timed steps" % status)
+    if timed_draft_tokens <= 0:
+        raise RuntimeError("no draft tokens were produced")
+    return dict(wall_s=wall, event_ms=ev_ms, match_steps=timed_match_steps,
+                draft_tokens=timed_draft_tokens, init_s=init_s, build_s=build_s,
+                states=info[0], trans=info[1], static_bytes=info[2],
+                batch_bytes=sam.sam_batch_info(batch))
+
+
+def cpu_leg(w):
+    """The CPU checker as it stands, one thread, timed on the steps only."""
+    from oracle.sam_oracle import Batch, Sam
+    spec = w.spec
+    note = ""
+    corpus = w.corpus
+    limit = 20_000_000
+    if corpus is not None and len(corpus) > limit:
+        corpus = corpus[:limit]
+        note = "; corpus cut to its first %d tokens to bound the run" % limit
+    t0 = time.time()
+    static = Sam.build(corpus) if corpus is not None else None
+    build_s = time.time() - t0
+    nb = min(spec.batch, 64)
+    ob = Batch(static, corpus, [w.prompts[b] for b in range(nb)], spec.max_accept,
+               spec.draft_len, spec.l_bias)
+    acc = np.ascontiguousarray(w.accepted[:, :nb])
+    cnt = np.ascontiguousarray(w.counts[:, :nb])
+    t0 = time.perf_counter()
+    for s in range(w.steps):
+        ob.step(acc[s], cnt[s])
+    dt = time.perf_counter() - t0
+    ms = int(cnt.sum())
+    return dict(value=ms / dt, unit="match-steps/s", cores=1, kind="oracle",
+                sample="%d of %d sequences, whole %d-step schedule (%d match-steps); "
+                       "corpus build (%.1f s) and prompt ingest not timed%s"
+                       % (nb, spec.batch, w.steps, ms, build_s, note))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--config", default="cfg2", choices=sorted(CONFIGS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (sequences are independent and "
+              "would be sharded without communication); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if args.steps < 1 or args.warmup < 0:
+        print("bench.py: --steps must be >= 1 and --warmup >= 0", file=sys.stderr)
+        sys.exit(2)
+
+    spec = CONFIGS[args.config]
+    t0 = time.time()
+    w = make_workload(spec)
+    _log("%s: corpus %d tokens, batch %d, %d+%d tokens per sequence, %d steps in the schedule "
+         "(generated in %.1f s)" % (spec.name, spec.corpus_tokens, spec.batch, spec.prompt_len,
+                                    spec.gen_len, w.steps, time.time() - t0))
+    g = gpu_leg(w, args.steps, args.warmup)
+
+    per_step_ms = g["event_ms"] / args.steps
+    value = g["match_steps"] / (g["event_ms"] * 1e-3)
+    algo_bytes_per_launch = ALGO_BYTES_PER_MATCH_STEP[spec.name] * g["match_steps"] / args.steps
+    achieved = algo_bytes_per_launch / (per_step_ms * 1e-3) / 1e9
+    out = {
+        "metric": "SAM match-steps/sec (1 GPU)",
+        "value": value,
+        "unit": "match-steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": g["wall_s"] * 1e3 / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32",
+        "data": "synthetic",
+        "config": {
+            "workload": spec.name,
+            "corpus_tokens": spec.corpus_tokens,
+            "vocab": spec.vocab,
+            "batch": spec.batch,
+            "prompt_len": spec.prompt_len,
+            "gen_len": spec.gen_len,
+            "max_accept": spec.max_accept,
+            "draft_len": spec.draft_len,
+            "l_bias": spec.l_bias,
+            "seed": spec.seed,
+        },
+        "draft_tokens_per_s": g["draft_tokens"] / (g["event_ms"] * 1e-3),
+        "sequence_steps_per_s": spec.batch * args.steps / (g["event_ms"] * 1e-3),
+        "match_steps_timed": g["match_steps"],
+        "prompt_ingest_tokens_per_s": spec.batch * spec.prompt_len / g["init_s"],
+        "corpus_build_s": g["build_s"],
+        "device_bytes": {"static": g["static_bytes"], "batch": g["batch_bytes"]},
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "sam_feed_kernel",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBPS,
+            "traffic": None,
+            "algo_bytes_per_launch": algo_bytes_per_launch,
+            "avg_launch_ms": per_step_ms,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_leg(w)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

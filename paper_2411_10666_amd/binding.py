@@ -101,7 +101,7 @@ class Corpus:
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
-        if h:
+        if h and _lib is not None:
             _lib.sam_corpus_free(h)
 
 
@@ -115,7 +115,7 @@ class Batch:
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
-        if h:
+        if h and _lib is not None:
             _lib.sam_batch_free(h)
 
 
@@ -190,6 +190,43 @@ def sam_batch_step(batch: Batch, accepted, counts, match_len, draft, draft_len, 
                                _dev_ptr(draft, i32, "draft"),
                                _dev_ptr(draft_len, i32, "draft_len"),
                                _dev_ptr(source, i32, "source"), _stream_ptr(stream)))
+
+
+class StepPlan:
+    """Pre-marshalled arguments for a run of ``sam_batch_step`` calls, one per row
+    of the given [steps, ...] device tensors, so that a tight loop pays for the
+    C call only.  The tensors are kept alive by the plan."""
+
+    def __init__(self, batch: Batch, accepted, counts, match_len, draft, draft_len, source,
+                 stream=None):
+        import torch
+        i32 = torch.int32
+        S = int(counts.shape[0])
+        B, A, L = batch.batch, batch.max_accept, batch.draft_len
+        shapes = ((accepted, (S, B, A), "accepted"), (counts, (S, B), "counts"),
+                  (match_len, (S, B), "match_len"), (draft, (S, B, L), "draft"),
+                  (draft_len, (S, B), "draft_len"), (source, (S, B), "source"))
+        for t, shp, name in shapes:
+            _dev_ptr(t, i32, name)
+            if tuple(t.shape) != shp:
+                raise ValueError("%s must have shape %s" % (name, shp))
+        self._keep = [t for t, _, _ in shapes]
+        self._batch = batch
+        self._stream = _stream_ptr(stream)
+        self.steps = S
+        self._args = []
+        for s in range(S):
+            self._args.append(tuple(C.c_void_p(t.data_ptr() + s * t.stride(0) * 4)
+                                    for t, _, _ in shapes))
+
+    def run(self, lo: int, hi: int) -> None:
+        """Enqueue steps lo .. hi-1."""
+        fn, h, st, args = _lib.sam_batch_step, self._batch._h, self._stream, self._args
+        for s in range(lo, hi):
+            a = args[s]
+            rc = fn(h, a[0], a[1], a[2], a[3], a[4], a[5], st)
+            if rc != SAM_OK:
+                _check(rc)
 
 
 def sam_batch_debug(batch: Batch, s1, l1, s2, l2, stream=None) -> None:

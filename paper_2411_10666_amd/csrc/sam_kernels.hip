@@ -31,6 +31,13 @@ __device__ __forceinline__ uint32_t lane_get(uint32_t v, int src_lane)
     return (uint32_t)__builtin_amdgcn_readlane((int)v, src_lane);
 }
 
+// Keep a wave-uniform value materialised at this point of the program, so the
+// load that produced it cannot be moved below.
+__device__ __forceinline__ void pin_s(uint32_t &v)
+{
+    asm volatile("" : "+s"(v));
+}
+
 __device__ __forceinline__ void order_memory()
 {
     // stores and later loads of one wavefront reach memory in program order;
@@ -50,9 +57,10 @@ __device__ __forceinline__ void static_transfer(const StaticView &S, uint32_t t,
     for (uint32_t guard = l + 2; ; guard--) {
         if (guard == 0) { fault |= SAM_STATUS_INTERNAL_BIT; s = 0; l = 0; e = 0; return; }
         if (s == 0) {
-            const RootEnt r = S.root[t];
-            const uint32_t d = uni(r.dst);
-            if (d) { s = d; e = uni(r.endpos); l = 1; }
+            const uint2 r = reinterpret_cast<const uint2 *>(S.root)[t];
+            uint32_t d = uni(r.x), ep = uni(r.y);
+            pin_s(ep);
+            if (d) { s = d; e = ep; l = 1; }
             else   { l = 0; e = 0; }
             return;
         }
@@ -60,10 +68,14 @@ __device__ __forceinline__ void static_transfer(const StaticView &S, uint32_t t,
         // needed on a miss, but then it is already here
         const LinkRec lr = S.linkrec[s];
         uint64_t b = bucket_of(hash_key(s, t), S.n_buckets);
+        uint4 sl = reinterpret_cast<const uint4 *>(S.slots)[b * kBucketSlots + (lane & 7)];
+        uint32_t mh = (uint32_t)__ballot(sl.x == s && sl.y == t) & 0xFFu;
+        uint32_t me = (uint32_t)__ballot(sl.x == kNil) & 0xFFu;
+        uint32_t nlink = uni(lr.link), nlen = uni(lr.lenlink);
+        pin_s(nlink);
+        pin_s(mh);
         bool hit = false;
         for (uint64_t left = S.n_buckets; left; left--) {
-            const uint4 sl = reinterpret_cast<const uint4 *>(S.slots)[b * kBucketSlots + (lane & 7)];
-            const uint32_t mh = (uint32_t)__ballot(sl.x == s && sl.y == t) & 0xFFu;
             if (mh) {
                 const int j = __builtin_ctz(mh);
                 s = lane_get(sl.z, j);
@@ -72,13 +84,15 @@ __device__ __forceinline__ void static_transfer(const StaticView &S, uint32_t t,
                 hit = true;
                 break;
             }
-            const uint32_t me = (uint32_t)__ballot(sl.x == kNil) & 0xFFu;
             if (me) break;
             b = (b + 1 == S.n_buckets) ? 0 : b + 1;
+            sl = reinterpret_cast<const uint4 *>(S.slots)[b * kBucketSlots + (lane & 7)];
+            mh = (uint32_t)__ballot(sl.x == s && sl.y == t) & 0xFFu;
+            me = (uint32_t)__ballot(sl.x == kNil) & 0xFFu;
         }
         if (hit) return;
-        s = uni(lr.link);
-        l = uni(lr.lenlink);
+        s = nlink;
+        l = nlen;
     }
 }
 
@@ -165,15 +179,38 @@ __device__ __forceinline__ bool dyn_probe(const DynSeq &D, uint32_t p, uint32_t 
     return resolve_probe(D, p, t, lane, b, issue_bucket(D, b, lane), at, dst);
 }
 
-// Record of p and the bucket of (p, t) fetched in one round trip.
+// Record of p and the bucket of (p, t) fetched in one round trip: both loads are
+// issued, then both are consumed in the same straight-line block (the first
+// ballots and the record's words), so neither can be sunk behind a branch that
+// depends on the other.
 __device__ __forceinline__ bool rec_and_probe(const DynSeq &D, uint32_t p, uint32_t t, int lane,
                                               Rec &R, uint32_t &at, uint32_t &dst)
 {
     const RawRec raw = issue_rec(&D.rec[p]);
-    const uint32_t b = (uint32_t)bucket_of(hash_key(p, t), D.n_buckets);
-    const uint4 sl = issue_bucket(D, b, lane);
+    uint32_t b = (uint32_t)bucket_of(hash_key(p, t), D.n_buckets);
+    uint4 sl = issue_bucket(D, b, lane);
+    uint32_t mh = (uint32_t)__ballot(sl.x == p && sl.y == t) & 0xFFu;
+    uint32_t me = (uint32_t)__ballot(sl.x == kNil) & 0xFFu;
     R = finish_rec(raw);
-    return resolve_probe(D, p, t, lane, b, sl, at, dst);
+    pin_s(R.itok);
+    pin_s(mh);
+    for (uint32_t left = D.n_buckets; ; left--) {
+        if (mh) {
+            const int j = __builtin_ctz(mh);
+            at = b * kBucketSlots + j;
+            dst = lane_get(sl.z, j);
+            return true;
+        }
+        if (me) {
+            at = b * kBucketSlots + __builtin_ctz(me);
+            return false;
+        }
+        if (left == 0) { at = kNil; return false; }
+        b = (b + 1 == D.n_buckets) ? 0 : b + 1;
+        sl = issue_bucket(D, b, lane);
+        mh = (uint32_t)__ballot(sl.x == p && sl.y == t) & 0xFFu;
+        me = (uint32_t)__ballot(sl.x == kNil) & 0xFFu;
+    }
 }
 
 constexpr uint32_t kInline = 0xFFFFFFFEu;   // "the transition sits in the record"

@@ -1,0 +1,121 @@
+"""Full-size parity, in the launch configuration the benchmark times (the
+pre-marshalled step plan, back-to-back launches on one stream, outputs of every
+step kept): the whole schedule of a benchmark workload is run through the HIP
+library and every output of every step is compared with the CPU checker.
+
+Progress lines go to gpurun_out/test_progress.log so a long, quiet test can be
+told from a hung one."""
+import os
+import time
+
+import numpy as np
+import pytest
+
+from paper_2411_10666_amd.synth import CONFIGS, make_workload
+
+pytestmark = pytest.mark.gpu
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _say(msg):
+    d = os.path.join(ROOT, "gpurun_out")
+    os.makedirs(d, exist_ok=True)
+    with open(os.path.join(d, "test_progress.log"), "a") as f:
+        f.write("%s %s\n" % (time.strftime("%H:%M:%S"), msg))
+    print("[full] " + msg, flush=True)
+
+
+def _gpu_schedule(w, sequences=None):
+    """-> dict of [S, B(, L)] arrays + final cursors and sizes."""
+    import torch
+    from paper_2411_10666_amd import binding as sam
+    spec = w.spec
+    dev = torch.device("cuda:0")
+    t0 = time.time()
+    corpus = sam.sam_build(w.corpus, spec.vocab) if w.corpus is not None else None
+    _say("%s: library built the corpus automaton in %.1f s" % (spec.name, time.time() - t0))
+    B, A, L, S = spec.batch, spec.max_accept, spec.draft_len, w.steps
+    i32 = dict(dtype=torch.int32, device=dev)
+    batch = sam.sam_batch_init(corpus, torch.from_numpy(w.prompts.reshape(-1)).to(dev),
+                               torch.from_numpy(w.prompt_offsets).to(dev), B, spec.vocab,
+                               spec.max_seq_len, A, L, spec.l_bias)
+    acc = torch.from_numpy(w.accepted).to(dev)
+    cnt = torch.from_numpy(w.counts).to(dev)
+    ml = torch.zeros(S, B, **i32); dl = torch.zeros(S, B, **i32); src = torch.zeros(S, B, **i32)
+    dr = torch.zeros(S, B, L, **i32)
+    plan = sam.StepPlan(batch, acc, cnt, ml, dr, dl, src)
+    plan.run(0, S)
+    cur = [torch.empty(B, **i32) for _ in range(4)]
+    siz = [torch.empty(B, **i32) for _ in range(3)]
+    sam.sam_batch_debug(batch, *cur)
+    sam.sam_batch_sizes(batch, *siz)
+    torch.cuda.synchronize()
+    assert sam.sam_batch_status(batch) == 0
+    _say("%s: %d steps on the GPU done" % (spec.name, S))
+    return dict(match_len=ml.cpu().numpy(), draft_len=dl.cpu().numpy(), source=src.cpu().numpy(),
+                draft=dr.cpu().numpy(),
+                cursors=np.stack([c.cpu().numpy() for c in cur], axis=1),
+                sizes=np.stack([c.cpu().numpy() for c in siz], axis=1))
+
+
+def _oracle_schedule(w, seqs):
+    """The checker on the chosen sequences (all steps)."""
+    from oracle.sam_oracle import Batch, Sam
+    spec = w.spec
+    t0 = time.time()
+    static = Sam.build(w.corpus) if w.corpus is not None else None
+    _say("%s: checker built the corpus automaton in %.1f s" % (spec.name, time.time() - t0))
+    ob = Batch(static, w.corpus, [w.prompts[b] for b in seqs], spec.max_accept, spec.draft_len,
+               spec.l_bias)
+    S, nb, L = w.steps, len(seqs), spec.draft_len
+    out = dict(match_len=np.zeros((S, nb), np.int32), draft_len=np.zeros((S, nb), np.int32),
+               source=np.zeros((S, nb), np.int32), draft=np.zeros((S, nb, L), np.int32))
+    acc = np.ascontiguousarray(w.accepted[:, seqs])
+    cnt = np.ascontiguousarray(w.counts[:, seqs])
+    for s in range(S):
+        m, sr, d_l, d = ob.step(acc[s], cnt[s])
+        out["match_len"][s], out["source"][s], out["draft_len"][s], out["draft"][s] = m, sr, d_l, d
+    out["cursors"] = ob.cursors()
+    out["sizes"] = np.array([[q._L.oseq_text_len(q._h), q.dynamic().num_states,
+                              q.dynamic().num_trans] for q in ob.seqs], dtype=np.int32)
+    _say("%s: checker ran %d sequences" % (spec.name, nb))
+    return out
+
+
+def _compare(g, r, seqs, has_static=True):
+    for k in ("match_len", "draft_len", "source"):
+        assert np.array_equal(g[k][:, seqs], r[k]), k
+    assert np.array_equal(g["draft"][:, seqs], r["draft"])
+    assert np.array_equal(g["sizes"][seqs], r["sizes"])
+    gc, rc = g["cursors"][seqs], r["cursors"]
+    if not has_static:
+        gc, rc = gc[:, 2:], rc[:, 2:]
+    assert np.array_equal(gc, rc)
+
+
+def test_cfg2_full_schedule_every_output():
+    spec = CONFIGS["cfg2"]
+    w = make_workload(spec)
+    g = _gpu_schedule(w)
+    seqs = list(range(spec.batch))
+    r = _oracle_schedule(w, seqs)
+    _compare(g, r, seqs)
+    assert (r["source"] == 2).sum() > 1000 and (r["source"] == 1).sum() > 100
+
+
+def test_cfg4_full_batch_dynamic_only():
+    """All 1024 sequences on the GPU at full length; the checker replays every
+    16th sequence plus the first and last."""
+    spec = CONFIGS["cfg4"]
+    w = make_workload(spec)
+    g = _gpu_schedule(w)
+    seqs = sorted(set(list(range(0, spec.batch, 16)) + [1, spec.batch - 1]))
+    r = _oracle_schedule(w, seqs)
+    _compare(g, r, seqs, has_static=False)
+    # properties that hold for every sequence at any size
+    T = spec.max_seq_len
+    assert (g["sizes"][:, 0] == T).all()
+    assert (g["sizes"][:, 1] <= 2 * T - 1).all() and (g["sizes"][:, 2] <= 3 * T - 4).all()
+    assert (g["draft_len"] <= spec.draft_len).all() and (g["match_len"] >= 0).all()
+    assert ((g["source"] == 0) == (g["match_len"] == 0)).all()
