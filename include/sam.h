@@ -120,8 +120,10 @@ void sam_corpus_free(sam_corpus *corpus);
  *   vocab          : token range when corpus is NULL; ignored (the corpus's
  *                    vocabulary is used) otherwise.
  *   max_seq_len    : capacity of every sequence (prompt + generated tokens),
- *                    1 .. 2^30.  Device memory is reserved for the worst case
- *                    of 2*max_seq_len states and 3*max_seq_len transitions.
+ *                    1 .. 2^28.  Device memory is reserved for the worst case
+ *                    (2*max_seq_len states; at most max_seq_len transitions
+ *                    live outside the state records), so a sequence never
+ *                    runs out of table space before it runs out of length.
  *   max_accept     : row length of `accepted` in sam_batch_step, 1 .. 4096.
  *   draft_len      : draft tokens per sequence, 1 .. 1024.
  *   l_bias         : the static source is chosen only if l1 > l2 + l_bias.
@@ -174,6 +176,15 @@ int sam_batch_sizes(const sam_batch *batch, int32_t *text_len, int32_t *n_states
 
 /* OR of the SAM_STATUS_* bits raised so far.  Synchronises the stream. */
 int sam_batch_status(const sam_batch *batch, uint32_t *status, void *hip_stream);
+
+/*
+ * Testing aid.  Per-sequence tables come in two layouts: a compact one (16-bit
+ * state ids; chosen when max_seq_len <= 16366 and vocab <= 131072) and a wide
+ * one (32-bit ids, any size).  mode 1 makes every later sam_batch_init in this
+ * process use the wide layout, mode 0 restores the automatic choice.  Results
+ * are identical either way.
+ */
+int sam_set_layout_override(int mode);
 
 /* Bytes of device memory the batch holds. */
 int sam_batch_info(const sam_batch *batch, int64_t *device_bytes);

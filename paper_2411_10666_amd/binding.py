@@ -23,7 +23,7 @@ EXPORTS = [
     "sam_last_error", "sam_build", "sam_build_host_only", "sam_corpus_info",
     "sam_corpus_export", "sam_corpus_find", "sam_corpus_free", "sam_batch_init",
     "sam_batch_step", "sam_batch_debug", "sam_batch_sizes", "sam_batch_status",
-    "sam_batch_info", "sam_batch_free",
+    "sam_batch_info", "sam_batch_free", "sam_set_layout_override",
 ]
 
 
@@ -54,6 +54,7 @@ def _load():
     L.sam_batch_sizes.argtypes = [vp, vp, vp, vp, vp]
     L.sam_batch_status.argtypes = [vp, C.POINTER(C.c_uint32), vp]
     L.sam_batch_info.argtypes = [vp, C.POINTER(i64)]
+    L.sam_set_layout_override.argtypes = [C.c_int]
     L.sam_batch_free.argtypes = [vp]
     L.sam_batch_free.restype = None
     for name in EXPORTS:
@@ -249,6 +250,10 @@ def sam_batch_status(batch: Batch, stream=None) -> int:
     st = C.c_uint32()
     _check(_lib.sam_batch_status(batch._h, C.byref(st), _stream_ptr(stream)))
     return st.value
+
+
+def sam_set_layout_override(mode: int) -> None:
+    _check(_lib.sam_set_layout_override(mode))
 
 
 def sam_batch_info(batch: Batch) -> int:

@@ -19,6 +19,7 @@ using namespace sam;
 namespace {
 
 thread_local std::string g_err;
+int g_layout_override = 0;   // 0: pick per batch, 1: always the wide layout
 
 int fail(int code, const std::string &msg)
 {
@@ -203,8 +204,8 @@ int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
     if (!prompt_tokens || !prompt_offsets)
         return fail(SAM_EINVAL, "sam_batch_init: prompt_tokens / prompt_offsets is NULL");
     if (batch < 1) return fail(SAM_EINVAL, "sam_batch_init: batch must be >= 1");
-    if (max_seq_len < 1 || max_seq_len > (1 << 30))
-        return fail(SAM_EINVAL, "sam_batch_init: max_seq_len must be in 1 .. 2^30");
+    if (max_seq_len < 1 || max_seq_len > (1 << 28))
+        return fail(SAM_EINVAL, "sam_batch_init: max_seq_len must be in 1 .. 2^28");
     if (max_accept < 1 || max_accept > 4096)
         return fail(SAM_EINVAL, "sam_batch_init: max_accept must be in 1 .. 4096");
     if (draft_len < 1 || draft_len > 1024)
@@ -243,14 +244,19 @@ int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
     v.vocab = vocab;
     v.max_seq_len = (uint32_t)max_seq_len;
     v.max_states = 2u * (uint32_t)max_seq_len + 2u;
-    v.dyn_buckets = (uint32_t)dynamic_buckets_for(max_seq_len);
+    v.compact = (g_layout_override == 0 && max_seq_len <= kCompactMaxSeqLen &&
+                 vocab <= kCompactMaxVocab) ? 1 : 0;
+    const uint64_t dyn_slots = dynamic_slots_for(max_seq_len);
+    const size_t slot_bytes = v.compact ? sizeof(SlotCompact) : sizeof(Slot);
+    const size_t rec_bytes = v.compact ? sizeof(DynRecCompact) : sizeof(DynRec);
+    v.dyn_buckets = (uint32_t)(dyn_slots * slot_bytes / 128);
     v.max_accept = max_accept;
     v.draft_len = draft_len;
     v.l_bias = l_bias;
     v.has_static = corpus ? 1 : 0;
     const size_t b_text = (size_t)batch * max_seq_len * sizeof(int32_t);
-    const size_t b_rec = (size_t)batch * v.max_states * sizeof(DynRec);
-    const size_t b_slots = (size_t)batch * v.dyn_buckets * kBucketSlots * sizeof(Slot);
+    const size_t b_rec = (size_t)batch * v.max_states * rec_bytes;
+    const size_t b_slots = (size_t)batch * v.dyn_buckets * 128;
     const size_t b_meta = (size_t)batch * sizeof(SeqMeta);
     hipError_t e;
     if ((e = hipMalloc((void **)&v.dyn_text, b_text)) != hipSuccess ||
@@ -325,6 +331,13 @@ int sam_batch_status(const sam_batch *bt, uint32_t *status, void *hip_stream)
     HIP_TRY(hipMemcpyAsync(status, bt->view.status, sizeof(uint32_t), hipMemcpyDeviceToHost,
                            stream));
     HIP_TRY(hipStreamSynchronize(stream));
+    return SAM_OK;
+}
+
+int sam_set_layout_override(int mode)
+{
+    if (mode != 0 && mode != 1) return fail(SAM_EINVAL, "sam_set_layout_override: mode is 0 or 1");
+    g_layout_override = mode;
     return SAM_OK;
 }
 

@@ -29,14 +29,15 @@ struct BatchView {
     int32_t   vocab;
     uint32_t  max_seq_len;
     uint32_t  max_states;      // records per sequence (2 * max_seq_len + 2)
-    uint32_t  dyn_buckets;     // buckets per sequence
+    uint32_t  dyn_buckets;     // 128-byte buckets per sequence
+    int32_t   compact;         // 1: DynRecCompact / SlotCompact, 0: DynRec / Slot
     int32_t   max_accept;
     int32_t   draft_len;
     int32_t   l_bias;
     int32_t   has_static;
     int32_t  *dyn_text;        // [batch, max_seq_len]
-    DynRec   *dyn_rec;         // [batch, max_states]
-    Slot     *dyn_slots;       // [batch, dyn_buckets * 8]
+    void     *dyn_rec;         // [batch, max_states] records of the chosen layout
+    void     *dyn_slots;       // [batch, dyn_buckets] buckets of 128 bytes
     SeqMeta  *meta;            // [batch]
     uint32_t *status;          // [1]
 };

@@ -8,10 +8,14 @@
 // both over the same accepted tokens and concurrently; they meet at one
 // barrier, after which wave 0 selects the source and gathers the draft with
 // coalesced reads.  Inside a wave all control flow is wave-uniform: the lanes
-// are used to fetch a whole 128-byte hash bucket (8 slots) in one request and
-// to resolve it with a ballot, so a lookup costs one memory round trip whatever
-// the state's out-degree.  Sequence b is always served by workgroup b, so its
-// private tables keep hitting the L2 of the same XCD from launch to launch.
+// are used to fetch a whole 128-byte hash bucket in one request and to resolve
+// it with two ballots, so a lookup costs one memory round trip whatever the
+// state's out-degree.  The path is bound by dependent memory round trips, so
+// the code is organised around them: every load whose address is known is
+// issued before the wave waits for any of them, and the first lookup of the
+// next token is issued together with the last read of the current one.
+// Sequence b is always served by workgroup b, so its private tables keep
+// hitting the L2 of the same XCD from launch to launch.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -96,135 +100,241 @@ __device__ __forceinline__ void static_transfer(const StaticView &S, uint32_t t,
     }
 }
 
+// ---- dynamic automaton: the two table layouts ------------------------------
+
+struct Rec {              // a state record held in wave-uniform registers
+    uint32_t len, link, endpos, head, itok, idst;     // kNil = none
+};
+
+// 32-byte records, 16-byte slots, 8 slots per bucket: any length, any vocabulary
+struct WideDyn {
+    static constexpr int kSlots = 8;
+    struct RawRec { uint4 a; uint2 b; };
+    typedef uint4 RawSlot;
+
+    static __device__ __forceinline__ RawRec issue_rec(const void *rec, uint32_t s)
+    {
+        const DynRec *r = reinterpret_cast<const DynRec *>(rec) + s;
+        RawRec w;
+        w.a = reinterpret_cast<const uint4 *>(r)[0];
+        w.b = reinterpret_cast<const uint2 *>(r)[2];
+        return w;
+    }
+    static __device__ __forceinline__ Rec finish_rec(const RawRec &w)
+    {
+        Rec R;
+        R.len = uni(w.a.x); R.link = uni(w.a.y); R.endpos = uni(w.a.z); R.head = uni(w.a.w);
+        R.itok = uni(w.b.x); R.idst = uni(w.b.y);
+        return R;
+    }
+    static __device__ __forceinline__ void store_rec(void *rec, uint32_t s, const Rec &R)
+    {
+        DynRec *r = reinterpret_cast<DynRec *>(rec) + s;
+        reinterpret_cast<uint4 *>(r)[0] = make_uint4(R.len, R.link, R.endpos, R.head);
+        reinterpret_cast<uint2 *>(r)[2] = make_uint2(R.itok, R.idst);
+    }
+    static __device__ __forceinline__ void store_inline(void *rec, uint32_t s, uint32_t tok,
+                                                        uint32_t dst)
+    {
+        reinterpret_cast<uint2 *>(reinterpret_cast<DynRec *>(rec) + s)[2] = make_uint2(tok, dst);
+    }
+    static __device__ __forceinline__ void store_head(void *rec, uint32_t s, uint32_t head)
+    {
+        (reinterpret_cast<DynRec *>(rec) + s)->head = head;
+    }
+    static __device__ __forceinline__ void store_link(void *rec, uint32_t s, uint32_t link)
+    {
+        (reinterpret_cast<DynRec *>(rec) + s)->link = link;
+    }
+    static __device__ __forceinline__ void store_idst(void *rec, uint32_t s, uint32_t dst)
+    {
+        (reinterpret_cast<DynRec *>(rec) + s)->idst = dst;
+    }
+    static __device__ __forceinline__ RawSlot issue_slot(const void *slots, uint32_t idx)
+    {
+        return reinterpret_cast<const uint4 *>(slots)[idx];
+    }
+    static __device__ __forceinline__ bool slot_is(const RawSlot &sl, uint32_t p, uint32_t t)
+    {
+        return sl.x == p && sl.y == t;
+    }
+    static __device__ __forceinline__ bool slot_empty(const RawSlot &sl) { return sl.x == kNil; }
+    static __device__ __forceinline__ uint32_t slot_dst(const RawSlot &sl) { return sl.z; }
+    static __device__ __forceinline__ uint32_t slot_token(const RawSlot &sl) { return sl.y; }
+    static __device__ __forceinline__ uint32_t slot_next(const RawSlot &sl) { return sl.w; }
+    static __device__ __forceinline__ void store_slot(void *slots, uint32_t idx, uint32_t p,
+                                                      uint32_t t, uint32_t dst, uint32_t next)
+    {
+        reinterpret_cast<uint4 *>(slots)[idx] = make_uint4(p, t, dst, next);
+    }
+    static __device__ __forceinline__ void store_slot_dst(void *slots, uint32_t idx, uint32_t dst)
+    {
+        reinterpret_cast<Slot *>(slots)[idx].dst = dst;
+    }
+};
+
+// 16-byte records, 8-byte slots, 16 slots per bucket: 15-bit state ids
+struct CompactDyn {
+    static constexpr int kSlots = 16;
+    typedef uint4 RawRec;
+    typedef uint2 RawSlot;
+
+    static __device__ __forceinline__ uint32_t widen(uint32_t v16)
+    {
+        return v16 == 0xFFFFu ? kNil : v16;
+    }
+    static __device__ __forceinline__ RawRec issue_rec(const void *rec, uint32_t s)
+    {
+        return reinterpret_cast<const uint4 *>(rec)[s];
+    }
+    static __device__ __forceinline__ Rec finish_rec(const RawRec &w)
+    {
+        const uint32_t a = uni(w.x), b = uni(w.y);
+        Rec R;
+        R.len = a & 0xFFFFu; R.link = widen(a >> 16);
+        R.endpos = b & 0xFFFFu; R.head = widen(b >> 16);
+        R.itok = uni(w.z); R.idst = uni(w.w) & 0xFFFFu;
+        return R;
+    }
+    static __device__ __forceinline__ void store_rec(void *rec, uint32_t s, const Rec &R)
+    {
+        reinterpret_cast<uint4 *>(rec)[s] =
+            make_uint4((R.len & 0xFFFFu) | (R.link << 16), (R.endpos & 0xFFFFu) | (R.head << 16),
+                       R.itok, R.idst & 0xFFFFu);
+    }
+    static __device__ __forceinline__ void store_inline(void *rec, uint32_t s, uint32_t tok,
+                                                        uint32_t dst)
+    {
+        reinterpret_cast<uint2 *>(rec)[2 * s + 1] = make_uint2(tok, dst & 0xFFFFu);
+    }
+    static __device__ __forceinline__ void store_head(void *rec, uint32_t s, uint32_t head)
+    {
+        reinterpret_cast<uint16_t *>(rec)[8 * s + 3] = (uint16_t)head;
+    }
+    static __device__ __forceinline__ void store_link(void *rec, uint32_t s, uint32_t link)
+    {
+        reinterpret_cast<uint16_t *>(rec)[8 * s + 1] = (uint16_t)link;
+    }
+    static __device__ __forceinline__ void store_idst(void *rec, uint32_t s, uint32_t dst)
+    {
+        reinterpret_cast<uint16_t *>(rec)[8 * s + 6] = (uint16_t)dst;
+    }
+    static __device__ __forceinline__ RawSlot issue_slot(const void *slots, uint32_t idx)
+    {
+        return reinterpret_cast<const uint2 *>(slots)[idx];
+    }
+    static __device__ __forceinline__ bool slot_is(const RawSlot &sl, uint32_t p, uint32_t t)
+    {
+        return sl.x == ((p << 17) | t);
+    }
+    static __device__ __forceinline__ bool slot_empty(const RawSlot &sl) { return sl.x == kNil; }
+    static __device__ __forceinline__ uint32_t slot_dst(const RawSlot &sl) { return sl.y & 0xFFFFu; }
+    static __device__ __forceinline__ uint32_t slot_token(const RawSlot &sl) { return sl.x & 0x1FFFFu; }
+    static __device__ __forceinline__ uint32_t slot_next(const RawSlot &sl) { return widen(sl.y >> 16); }
+    static __device__ __forceinline__ void store_slot(void *slots, uint32_t idx, uint32_t p,
+                                                      uint32_t t, uint32_t dst, uint32_t next)
+    {
+        reinterpret_cast<uint2 *>(slots)[idx] =
+            make_uint2((p << 17) | t, (dst & 0xFFFFu) | (next << 16));
+    }
+    static __device__ __forceinline__ void store_slot_dst(void *slots, uint32_t idx, uint32_t dst)
+    {
+        reinterpret_cast<uint16_t *>(slots)[4 * idx + 2] = (uint16_t)dst;
+    }
+};
+
 // ---- dynamic automaton: Expand (Algorithm 2) ------------------------------
 
 struct DynSeq {
     int32_t *text;
-    DynRec  *rec;
-    Slot    *slots;
+    void    *rec;
+    void    *slots;
     uint32_t n_buckets;
 };
 
-struct Rec {              // a DynRec held in wave-uniform registers
-    uint32_t len, link, endpos, head, itok, idst;
+// A lookup of (p, t) in the slot table whose home bucket has been fetched and
+// reduced to two lane masks: mh = slots holding the key, me = empty slots.
+template <class L>
+struct Probe {
+    uint32_t b;
+    typename L::RawSlot sl;
+    uint32_t mh, me;
 };
 
-struct RawRec { uint4 a; uint2 b; };
-
-__device__ __forceinline__ RawRec issue_rec(const DynRec *r)
+template <class L>
+__device__ __forceinline__ typename L::RawSlot issue_bucket(const DynSeq &D, uint32_t b, int lane)
 {
-    RawRec w;
-    w.a = reinterpret_cast<const uint4 *>(r)[0];
-    w.b = reinterpret_cast<const uint2 *>(r)[2];
-    return w;
+    return L::issue_slot(D.slots, b * L::kSlots + (lane & (L::kSlots - 1)));
 }
 
-__device__ __forceinline__ Rec finish_rec(const RawRec &w)
+template <class L>
+__device__ __forceinline__ void reduce_bucket(Probe<L> &P, uint32_t p, uint32_t t)
 {
-    const uint4 a = w.a;
-    const uint2 b = w.b;
-    Rec R;
-    R.len = uni(a.x); R.link = uni(a.y); R.endpos = uni(a.z); R.head = uni(a.w);
-    R.itok = uni(b.x); R.idst = uni(b.y);
-    return R;
+    constexpr uint32_t kMask = (1u << L::kSlots) - 1u;
+    P.mh = (uint32_t)__ballot(L::slot_is(P.sl, p, t)) & kMask;
+    P.me = (uint32_t)__ballot(L::slot_empty(P.sl)) & kMask;
 }
 
-__device__ __forceinline__ Rec load_rec(const DynRec *r) { return finish_rec(issue_rec(r)); }
-
-__device__ __forceinline__ void store_rec(DynRec *r, const Rec &R, int lane)
+// Finish a lookup.  Hit: returns true, `at` = slot index, `dst` = target.
+// Miss: returns false, `at` = first empty slot on the probe path (where an
+// insert of this key goes; kNil if a full sweep found none, which the sizing
+// of the table excludes).
+template <class L>
+__device__ __forceinline__ bool resolve_probe(const DynSeq &D, Probe<L> P, uint32_t p, uint32_t t,
+                                              int lane, uint32_t &at, uint32_t &dst)
 {
-    if (lane == 0) {
-        reinterpret_cast<uint4 *>(r)[0] = make_uint4(R.len, R.link, R.endpos, R.head);
-        reinterpret_cast<uint2 *>(r)[2] = make_uint2(R.itok, R.idst);
-    }
-}
-
-// Look (p, t) up in the sequence's slot table.  Hit: returns true, `at` = slot
-// index, `dst` = target.  Miss: returns false, `at` = first empty slot on the
-// probe path (where an insert of this key goes).  `sl` is the already issued
-// load of the key's home bucket (see issue_bucket).
-__device__ __forceinline__ uint4 issue_bucket(const DynSeq &D, uint32_t b, int lane)
-{
-    return reinterpret_cast<const uint4 *>(D.slots)[b * kBucketSlots + (lane & 7)];
-}
-
-__device__ __forceinline__ bool resolve_probe(const DynSeq &D, uint32_t p, uint32_t t, int lane,
-                                              uint32_t b, uint4 sl, uint32_t &at, uint32_t &dst)
-{
-    // the table always has empty slots (at most 3/4 full), so this ends long
-    // before the bound; a full sweep reports "absent, nowhere to insert"
     for (uint32_t left = D.n_buckets; ; left--) {
-        if (left == 0) { at = kNil; return false; }
-        const uint32_t mh = (uint32_t)__ballot(sl.x == p && sl.y == t) & 0xFFu;
-        if (mh) {
-            const int j = __builtin_ctz(mh);
-            at = b * kBucketSlots + j;
-            dst = lane_get(sl.z, j);
+        if (P.mh) {
+            const int j = __builtin_ctz(P.mh);
+            at = P.b * L::kSlots + j;
+            dst = lane_get(L::slot_dst(P.sl), j);
             return true;
         }
-        const uint32_t me = (uint32_t)__ballot(sl.x == kNil) & 0xFFu;
-        if (me) {
-            at = b * kBucketSlots + __builtin_ctz(me);
+        if (P.me) {
+            at = P.b * L::kSlots + __builtin_ctz(P.me);
             return false;
         }
-        b = (b + 1 == D.n_buckets) ? 0 : b + 1;
-        sl = issue_bucket(D, b, lane);
+        if (left == 0) { at = kNil; return false; }
+        P.b = (P.b + 1 == D.n_buckets) ? 0 : P.b + 1;
+        P.sl = issue_bucket<L>(D, P.b, lane);
+        reduce_bucket<L>(P, p, t);
     }
 }
 
-__device__ __forceinline__ bool dyn_probe(const DynSeq &D, uint32_t p, uint32_t t, int lane,
-                                          uint32_t &at, uint32_t &dst)
+// Record of p and the home bucket of (p, t) in one round trip: both loads are
+// issued, then both are consumed in the same straight-line block, so neither
+// can be sunk behind a branch that depends on the other.
+template <class L>
+__device__ __forceinline__ void rec_and_probe(const DynSeq &D, uint32_t p, uint32_t t, int lane,
+                                              Rec &R, Probe<L> &P)
 {
-    const uint32_t b = (uint32_t)bucket_of(hash_key(p, t), D.n_buckets);
-    return resolve_probe(D, p, t, lane, b, issue_bucket(D, b, lane), at, dst);
-}
-
-// Record of p and the bucket of (p, t) fetched in one round trip: both loads are
-// issued, then both are consumed in the same straight-line block (the first
-// ballots and the record's words), so neither can be sunk behind a branch that
-// depends on the other.
-__device__ __forceinline__ bool rec_and_probe(const DynSeq &D, uint32_t p, uint32_t t, int lane,
-                                              Rec &R, uint32_t &at, uint32_t &dst)
-{
-    const RawRec raw = issue_rec(&D.rec[p]);
-    uint32_t b = (uint32_t)bucket_of(hash_key(p, t), D.n_buckets);
-    uint4 sl = issue_bucket(D, b, lane);
-    uint32_t mh = (uint32_t)__ballot(sl.x == p && sl.y == t) & 0xFFu;
-    uint32_t me = (uint32_t)__ballot(sl.x == kNil) & 0xFFu;
-    R = finish_rec(raw);
+    const typename L::RawRec raw = L::issue_rec(D.rec, p);
+    P.b = (uint32_t)bucket_of(hash_key(p, t), D.n_buckets);
+    P.sl = issue_bucket<L>(D, P.b, lane);
+    reduce_bucket<L>(P, p, t);
+    R = L::finish_rec(raw);
     pin_s(R.itok);
-    pin_s(mh);
-    for (uint32_t left = D.n_buckets; ; left--) {
-        if (mh) {
-            const int j = __builtin_ctz(mh);
-            at = b * kBucketSlots + j;
-            dst = lane_get(sl.z, j);
-            return true;
-        }
-        if (me) {
-            at = b * kBucketSlots + __builtin_ctz(me);
-            return false;
-        }
-        if (left == 0) { at = kNil; return false; }
-        b = (b + 1 == D.n_buckets) ? 0 : b + 1;
-        sl = issue_bucket(D, b, lane);
-        mh = (uint32_t)__ballot(sl.x == p && sl.y == t) & 0xFFu;
-        me = (uint32_t)__ballot(sl.x == kNil) & 0xFFu;
-    }
+    pin_s(P.mh);
 }
 
 constexpr uint32_t kInline = 0xFFFFFFFEu;   // "the transition sits in the record"
 
+template <class L>
 struct DynCursor {
     uint32_t n, n_states, last, n_trans;
-    uint32_t s2, l2, e2;      // link(last), its length, its min_endpos
+    uint32_t P;               // link(last); kNil while the sequence is empty
+    Rec      RP;              // record of P, kept in step with memory
+    bool     pf_ok;           // pf is the reduced home bucket of (P, next token)
+    Probe<L> pf;
 };
 
-// Append token t (Algorithm 2).  Afterwards (s2, l2) is the state and length of
-// the longest suffix of the sequence that also ends earlier in it, which is
-// what the paper's Transfer-then-Expand order leaves in the dynamic cursor.
-__device__ __forceinline__ void dyn_expand(const DynSeq &D, uint32_t t, int lane, DynCursor &c,
-                                           uint32_t &fault)
+// Append token t (Algorithm 2); tn is the token after it (kNil if unknown).
+// Afterwards P = link(last) is the state of the longest suffix of the sequence
+// that also ends earlier in it, with length RP.len: what the paper's
+// Transfer-then-Expand order leaves in the dynamic cursor.
+template <class L>
+__device__ __forceinline__ void dyn_expand(const DynSeq &D, uint32_t t, uint32_t tn, int lane,
+                                           DynCursor<L> &c, uint32_t &fault)
 {
     // Suffix links strictly shorten, so every chain below ends at the root after
     // fewer than n_states moves; `guard` turns a corrupted table into a status
@@ -233,113 +343,151 @@ __device__ __forceinline__ void dyn_expand(const DynSeq &D, uint32_t t, int lane
     const uint32_t k = c.n + 1;
     const uint32_t cur = c.n_states++;
     const uint32_t last = c.last;
+    const bool writer = lane == 0;
 
     // `last` never has a transition yet: its first one goes inline
-    if (lane == 0)
-        reinterpret_cast<uint2 *>(&D.rec[last])[2] = make_uint2(t, cur);
+    if (writer) L::store_inline(D.rec, last, t, cur);
     c.n_trans++;
     order_memory();
 
-    uint32_t p = c.s2;
-    if (last == 0) p = kNil;               // root's link
-    Rec R = {};
-    uint32_t q = kNil, where = kNil;
-    while (p != kNil) {
-        if (--guard == 0) { fault |= SAM_STATUS_INTERNAL_BIT; p = kNil; break; }
-        uint32_t at, dst;
-        const bool hit = rec_and_probe(D, p, t, lane, R, at, dst);
-        if (R.itok == t) { q = R.idst; where = kInline; break; }
-        if (hit)         { q = dst;    where = at;      break; }
-        if (R.itok == kNil) {
-            if (lane == 0)
-                reinterpret_cast<uint2 *>(&D.rec[p])[2] = make_uint2(t, cur);
-        } else if (at == kNil) {
-            fault |= SAM_STATUS_INTERNAL_BIT;
-        } else {
-            if (lane == 0) {
-                reinterpret_cast<uint4 *>(D.slots)[at] = make_uint4(p, t, cur, R.head);
-                D.rec[p].head = at;
-            }
-        }
-        c.n_trans++;
-        order_memory();
-        p = R.link;
-    }
+    uint32_t newP;
+    Rec newRP;
+    bool new_pf_ok = false;
+    Probe<L> new_pf = c.pf;
 
-    uint32_t linkc, l2, e2;
-    if (p == kNil) {
-        linkc = 0; l2 = 0; e2 = 0;
+    if (c.P == kNil) {
+        // first token of the sequence: last is the root, which now has (t -> cur)
+        newP = 0;
+        newRP.len = 0; newRP.link = kNil; newRP.endpos = 0; newRP.head = kNil;
+        newRP.itok = t; newRP.idst = cur;
     } else {
-        Rec Q = load_rec(&D.rec[q]);
-        if (q == last) { Q.itok = t; Q.idst = cur; }
-        if (R.len + 1 == Q.len) {
-            linkc = q; l2 = Q.len; e2 = Q.endpos;
+        uint32_t p = c.P;
+        Rec R = c.RP;
+        Probe<L> pr;
+        if (c.pf_ok) {
+            pr = c.pf;
         } else {
-            const uint32_t cl = c.n_states++;
-            Rec CL;
-            CL.len = R.len + 1; CL.link = Q.link; CL.endpos = Q.endpos;
-            CL.head = kNil; CL.itok = Q.itok; CL.idst = Q.idst;
-            if (Q.itok != kNil) c.n_trans++;
-            // copy q's further transitions
-            for (uint32_t j = Q.head; j != kNil;) {
-                if (--guard == 0 || j >= D.n_buckets * kBucketSlots) {
-                    fault |= SAM_STATUS_INTERNAL_BIT;
-                    break;
+            pr.b = (uint32_t)bucket_of(hash_key(p, t), D.n_buckets);
+            pr.sl = issue_bucket<L>(D, pr.b, lane);
+            reduce_bucket<L>(pr, p, t);
+        }
+        uint32_t q = kNil, where = kNil;
+        // give t-transitions to the states on last's suffix path that lack one
+        for (;;) {
+            if (--guard == 0) { fault |= SAM_STATUS_INTERNAL_BIT; p = kNil; break; }
+            if (R.itok == t) { q = R.idst; where = kInline; break; }
+            uint32_t at, dst;
+            if (resolve_probe<L>(D, pr, p, t, lane, at, dst)) { q = dst; where = at; break; }
+            if (R.itok == kNil) {
+                if (writer) L::store_inline(D.rec, p, t, cur);
+                R.itok = t; R.idst = cur;
+            } else if (at == kNil) {
+                fault |= SAM_STATUS_INTERNAL_BIT;
+            } else {
+                if (writer) {
+                    L::store_slot(D.slots, at, p, t, cur, R.head);
+                    L::store_head(D.rec, p, at);
                 }
-                const uint4 sl = reinterpret_cast<const uint4 *>(D.slots)[j];
-                const uint32_t tok = uni(sl.y), d = uni(sl.z);
-                j = uni(sl.w);
-                uint32_t at, dummy;
-                dyn_probe(D, cl, tok, lane, at, dummy);
-                if (at == kNil) { fault |= SAM_STATUS_INTERNAL_BIT; break; }
-                if (lane == 0)
-                    reinterpret_cast<uint4 *>(D.slots)[at] = make_uint4(cl, tok, d, CL.head);
-                CL.head = at;
-                c.n_trans++;
-                order_memory();
+                R.head = at;
             }
-            store_rec(&D.rec[cl], CL, lane);
+            c.n_trans++;
             order_memory();
-            // states further up the path that still lead to q now lead to the clone
-            for (;;) {
-                if (lane == 0) {
-                    if (where == kInline) D.rec[p].idst = cl;
-                    else D.slots[where].dst = cl;
-                }
-                order_memory();
-                p = R.link;
-                if (p == kNil) break;
-                if (--guard == 0) { fault |= SAM_STATUS_INTERNAL_BIT; break; }
-                uint32_t at, dst;
-                const bool hit = rec_and_probe(D, p, t, lane, R, at, dst);
-                if (R.itok == t) {
-                    if (R.idst != q) break;
-                    where = kInline;
-                } else if (hit) {
-                    if (dst != q) break;
-                    where = at;
-                } else {
-                    break;
-                }
+            if (R.link == kNil) { p = kNil; break; }   // R stays the root's record
+            p = R.link;
+            rec_and_probe<L>(D, p, t, lane, R, pr);
+        }
+
+        if (p == kNil) {
+            newP = 0;
+            newRP = R;
+        } else {
+            // q's record, and with it the next token's first lookup (at q)
+            const typename L::RawRec rawq = L::issue_rec(D.rec, q);
+            if (tn != kNil) {
+                new_pf.b = (uint32_t)bucket_of(hash_key(q, tn), D.n_buckets);
+                new_pf.sl = issue_bucket<L>(D, new_pf.b, lane);
+                reduce_bucket<L>(new_pf, q, tn);
+                pin_s(new_pf.mh);
             }
-            if (lane == 0) D.rec[q].link = cl;
-            linkc = cl; l2 = CL.len; e2 = CL.endpos;
+            Rec Q = L::finish_rec(rawq);
+            pin_s(Q.len);
+            if (q == last) { Q.itok = t; Q.idst = cur; }
+            if (R.len + 1 == Q.len) {
+                newP = q;
+                newRP = Q;
+                new_pf_ok = tn != kNil;
+            } else {
+                const uint32_t cl = c.n_states++;
+                Rec CL;
+                CL.len = R.len + 1; CL.link = Q.link; CL.endpos = Q.endpos;
+                CL.head = kNil; CL.itok = Q.itok; CL.idst = Q.idst;
+                if (Q.itok != kNil) c.n_trans++;
+                // copy q's further transitions
+                for (uint32_t j = Q.head; j != kNil;) {
+                    if (--guard == 0 || j >= D.n_buckets * L::kSlots) {
+                        fault |= SAM_STATUS_INTERNAL_BIT;
+                        break;
+                    }
+                    const typename L::RawSlot sl = L::issue_slot(D.slots, j);
+                    const uint32_t tok = uni(L::slot_token(sl)), d = uni(L::slot_dst(sl));
+                    j = uni(L::slot_next(sl));
+                    Probe<L> pc;
+                    pc.b = (uint32_t)bucket_of(hash_key(cl, tok), D.n_buckets);
+                    pc.sl = issue_bucket<L>(D, pc.b, lane);
+                    reduce_bucket<L>(pc, cl, tok);
+                    uint32_t at, dummy;
+                    resolve_probe<L>(D, pc, cl, tok, lane, at, dummy);
+                    if (at == kNil) { fault |= SAM_STATUS_INTERNAL_BIT; break; }
+                    if (writer) L::store_slot(D.slots, at, cl, tok, d, CL.head);
+                    CL.head = at;
+                    c.n_trans++;
+                    order_memory();
+                }
+                if (writer) L::store_rec(D.rec, cl, CL);
+                order_memory();
+                // states further up the path that still lead to q now lead to the clone
+                for (;;) {
+                    if (writer) {
+                        if (where == kInline) L::store_idst(D.rec, p, cl);
+                        else L::store_slot_dst(D.slots, where, cl);
+                    }
+                    order_memory();
+                    p = R.link;
+                    if (p == kNil) break;
+                    if (--guard == 0) { fault |= SAM_STATUS_INTERNAL_BIT; break; }
+                    rec_and_probe<L>(D, p, t, lane, R, pr);
+                    if (R.itok == t) {
+                        if (R.idst != q) break;
+                        where = kInline;
+                    } else {
+                        uint32_t at, dst;
+                        if (!resolve_probe<L>(D, pr, p, t, lane, at, dst) || dst != q) break;
+                        where = at;
+                    }
+                }
+                if (writer) L::store_link(D.rec, q, cl);
+                newP = cl;
+                newRP = CL;
+            }
         }
     }
-    Rec C;
-    C.len = k; C.link = linkc; C.endpos = k; C.head = kNil; C.itok = kNil; C.idst = 0;
-    store_rec(&D.rec[cur], C, lane);
-    if (lane == 0) D.text[c.n] = (int32_t)t;
+    if (writer) {
+        Rec C;
+        C.len = k; C.link = newP; C.endpos = k; C.head = kNil; C.itok = kNil; C.idst = 0;
+        L::store_rec(D.rec, cur, C);
+        D.text[c.n] = (int32_t)t;
+    }
     order_memory();
-    c.n = k; c.last = cur; c.s2 = linkc; c.l2 = l2; c.e2 = e2;
+    c.n = k; c.last = cur; c.P = newP; c.RP = newRP; c.pf_ok = new_pf_ok; c.pf = new_pf;
 }
 
 }  // namespace
 
-// One workgroup (2 waves) per sequence.  offsets != NULL: ingest mode, sequence
-// b is fed tokens[offsets[b] : offsets[b+1]) and nothing is written to the
-// draft outputs.  Otherwise step mode: sequence b is fed the first counts[b]
-// tokens of tokens[b * max_accept ...], then source selection and draft gather.
+// One workgroup (2 waves) per sequence.  kIngest: sequence b is fed
+// tokens[offsets[b] : offsets[b+1]) and nothing is written to the draft
+// outputs.  Otherwise: sequence b is fed the first counts[b] tokens of
+// tokens[b * max_accept ...], then source selection and draft gather.
+template <class L, bool kIngest>
 __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B,
                                                         const int32_t *__restrict__ tokens,
                                                         const int64_t *__restrict__ offsets,
@@ -361,7 +509,7 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
     const int32_t *tok;
     int64_t count;
     uint32_t fault = 0;
-    if (offsets) {
+    if (kIngest) {
         const int64_t o0 = offsets[b], o1 = offsets[b + 1];
         tok = tokens + o0;
         count = o1 - o0;
@@ -392,27 +540,44 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
     } else {
         DynSeq D;
         D.text = B.dyn_text + (size_t)b * B.max_seq_len;
-        D.rec = B.dyn_rec + (size_t)b * B.max_states;
-        D.slots = B.dyn_slots + (size_t)b * B.dyn_buckets * kBucketSlots;
+        D.rec = reinterpret_cast<char *>(B.dyn_rec) +
+                (size_t)b * B.max_states * (B.compact ? sizeof(DynRecCompact) : sizeof(DynRec));
+        D.slots = reinterpret_cast<char *>(B.dyn_slots) + (size_t)b * B.dyn_buckets * 128;
         D.n_buckets = B.dyn_buckets;
-        DynCursor c;
+        DynCursor<L> c;
         c.n = n0; c.n_states = uni(meta->n_states); c.last = uni(meta->last);
         c.n_trans = uni(meta->n_trans);
-        c.s2 = uni(meta->s2); c.l2 = uni(meta->l2); c.e2 = uni(meta->e2);
+        c.P = uni(meta->s2);
+        c.RP.len = uni(meta->p_len); c.RP.link = uni(meta->p_link);
+        c.RP.endpos = uni(meta->p_endpos); c.RP.head = uni(meta->p_head);
+        c.RP.itok = uni(meta->p_itok); c.RP.idst = uni(meta->p_idst);
+        c.pf_ok = false;
+        c.pf.b = 0; c.pf.mh = 0; c.pf.me = 0;
+        c.pf.sl = typename L::RawSlot();
         bool stop = false;
         for (int64_t base = 0; base < count && !stop; base += 64) {
             const int m = (int)((count - base) < 64 ? (count - base) : 64);
             const uint32_t tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
+            c.pf_ok = false;
             for (int i = 0; i < m; i++) {
                 const uint32_t t = lane_get(tv, i);
                 if (t >= vocab) { stop = true; fault |= SAM_STATUS_TOKEN_BIT; break; }
-                dyn_expand(D, t, lane, c, fault);
+                uint32_t tn = kNil;
+                if (i + 1 < m) {
+                    tn = lane_get(tv, i + 1);
+                    if (tn >= vocab) tn = kNil;
+                }
+                dyn_expand<L>(D, t, tn, lane, c, fault);
             }
         }
         if (lane == 0) {
-            sh[3] = c.l2; sh[4] = c.e2; sh[5] = c.n;
-            meta->s2 = c.s2; meta->l2 = c.l2; meta->e2 = c.e2;
+            sh[3] = c.P == kNil ? 0u : c.RP.len;
+            sh[4] = c.P == kNil ? 0u : c.RP.endpos;
+            sh[5] = c.n;
             meta->n_states = c.n_states; meta->last = c.last; meta->n_trans = c.n_trans;
+            meta->s2 = c.P;
+            meta->p_len = c.RP.len; meta->p_link = c.RP.link; meta->p_endpos = c.RP.endpos;
+            meta->p_head = c.RP.head; meta->p_itok = c.RP.itok; meta->p_idst = c.RP.idst;
             if (fault) {
                 meta->status |= fault;
                 atomicOr(B.status, fault);
@@ -431,21 +596,21 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
         meta->s1 = s1; meta->l1 = l1; meta->e1 = e1;
         if (sh[6]) atomicOr(B.status, sh[6]);
     }
-    if (offsets) return;
+    if (kIngest) return;
 
     const bool use_static = B.has_static && ((int64_t)l1 > (int64_t)l2 + (int64_t)B.l_bias);
     const uint32_t ml = use_static ? l1 : l2;
     const uint32_t p = use_static ? e1 : e2;
     const int32_t *T = use_static ? S.text : B.dyn_text + (size_t)b * B.max_seq_len;
     const uint32_t Tn = use_static ? S.n_tokens : n1;
-    const int L = B.draft_len;
+    const int Ld = B.draft_len;
     int dl = 0;
     if (ml > 0) {
         const uint32_t room = Tn - p;
-        dl = room < (uint32_t)L ? (int)room : L;
+        dl = room < (uint32_t)Ld ? (int)room : Ld;
     }
-    for (int i = lane; i < L; i += 64)
-        draft[(size_t)b * L + i] = i < dl ? T[p + i] : -1;
+    for (int i = lane; i < Ld; i += 64)
+        draft[(size_t)b * Ld + i] = i < dl ? T[p + i] : -1;
     if (lane == 0) {
         match_len[b] = (int32_t)ml;
         draft_len[b] = dl;
@@ -459,12 +624,21 @@ __global__ void sam_reset_kernel(BatchView B)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B.batch) return;
-    DynRec r;
+    Rec r;
     r.len = 0; r.link = kNil; r.endpos = 0; r.head = kNil; r.itok = kNil; r.idst = 0;
-    r.pad0 = 0; r.pad1 = 0;
-    B.dyn_rec[(size_t)b * B.max_states] = r;
+    if (B.compact) {
+        CompactDyn::store_rec(reinterpret_cast<char *>(B.dyn_rec) +
+                                  (size_t)b * B.max_states * sizeof(DynRecCompact), 0, r);
+    } else {
+        void *base = reinterpret_cast<char *>(B.dyn_rec) + (size_t)b * B.max_states * sizeof(DynRec);
+        WideDyn::store_rec(base, 0, r);
+        DynRec *d = reinterpret_cast<DynRec *>(base);
+        d->pad0 = 0; d->pad1 = 0;
+    }
     SeqMeta m = {};
     m.n_states = 1;
+    m.s2 = kNil;
+    m.p_link = kNil; m.p_head = kNil; m.p_itok = kNil;
     B.meta[b] = m;
     if (b == 0) *B.status = 0;
 }
@@ -477,8 +651,8 @@ __global__ void sam_debug_kernel(BatchView B, int32_t *s1, int32_t *l1, int32_t 
     const SeqMeta m = B.meta[b];
     if (s1) s1[b] = (int32_t)m.s1;
     if (l1) l1[b] = (int32_t)m.l1;
-    if (s2) s2[b] = (int32_t)m.s2;
-    if (l2) l2[b] = (int32_t)m.l2;
+    if (s2) s2[b] = m.s2 == kNil ? 0 : (int32_t)m.s2;
+    if (l2) l2[b] = m.s2 == kNil ? 0 : (int32_t)m.p_len;
     if (text_len) text_len[b] = (int32_t)m.n;
     if (n_states) n_states[b] = (int32_t)m.n_states;
     if (n_trans) n_trans[b] = (int32_t)m.n_trans;
@@ -490,8 +664,22 @@ hipError_t launch_feed(const StaticView &S, const BatchView &B, const int32_t *t
                        const int64_t *offsets, const int32_t *counts, int32_t *match_len,
                        int32_t *draft, int32_t *draft_len, int32_t *source, hipStream_t stream)
 {
-    hipLaunchKernelGGL(sam_feed_kernel, dim3(B.batch), dim3(128), 0, stream, S, B, tokens,
-                       offsets, counts, match_len, draft, draft_len, source);
+    const dim3 grid(B.batch), block(128);
+    if (offsets) {
+        if (B.compact)
+            hipLaunchKernelGGL((sam_feed_kernel<CompactDyn, true>), grid, block, 0, stream, S, B,
+                               tokens, offsets, counts, match_len, draft, draft_len, source);
+        else
+            hipLaunchKernelGGL((sam_feed_kernel<WideDyn, true>), grid, block, 0, stream, S, B,
+                               tokens, offsets, counts, match_len, draft, draft_len, source);
+    } else {
+        if (B.compact)
+            hipLaunchKernelGGL((sam_feed_kernel<CompactDyn, false>), grid, block, 0, stream, S, B,
+                               tokens, offsets, counts, match_len, draft, draft_len, source);
+        else
+            hipLaunchKernelGGL((sam_feed_kernel<WideDyn, false>), grid, block, 0, stream, S, B,
+                               tokens, offsets, counts, match_len, draft, draft_len, source);
+    }
     return hipGetLastError();
 }
 

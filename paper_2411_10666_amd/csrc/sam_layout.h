@@ -12,14 +12,22 @@
 //                            linear over buckets; root's transitions are not
 //                            in it (they are in root[]).
 //
-//  dynamic automaton (one private region per sequence)
+//  dynamic automaton (one private region per sequence), two layouts:
 //    text[max_seq_len]       int32
-//    rec[2 * max_seq_len]    {length, link, min_endpos, head,
+//   wide (any max_seq_len, any vocabulary)
+//    rec[2 * max_seq_len+2]  {length, link, min_endpos, head,
 //                             itok, idst, -, -}                         32 B
-//                            itok/idst: the state's first transition, kept
-//                            inline; head: newest of its further transitions
-//                            in slots[], chained through Slot::w.
 //    slots[n_buckets * 8]    {state, token, target, next-in-state-list} 16 B
+//   compact (max_seq_len <= 16366 and vocab <= 2^17: 15-bit state ids)
+//    rec[2 * max_seq_len+2]  {length:16, link:16, min_endpos:16, head:16,
+//                             itok:32, idst:16, -:16}                   16 B
+//    slots[n_buckets * 16]   {key = state << 17 | token : 32,
+//                             target:16, next:16}                        8 B
+//   itok/idst: the state's first transition, kept inline; head: newest of its
+//   further transitions in slots[], chained through the slot's `next`.
+//   A sequence of T tokens has at most T - 1 transitions outside the records
+//   (transitions <= states + T - 2, and every state but the newest has one
+//   inline), so 2T slots keep the table at most half full.
 #pragma once
 #include <stdint.h>
 
@@ -59,13 +67,16 @@ struct DynRec {          // 32 B, dynamic automaton
 // per-sequence bookkeeping, 64 B
 struct SeqMeta {
     uint32_t s1, l1, e1;     // static cursor: state, match length, min_endpos(state)
-    uint32_t s2, l2, e2;     // dynamic cursor = link(last): state, its length, its min_endpos
     uint32_t n;              // tokens in the sequence so far
     uint32_t n_states;
     uint32_t last;
     uint32_t n_trans;
     uint32_t status;
-    uint32_t pad[5];
+    // dynamic cursor = link(last) and a copy of that state's record, so the
+    // next step starts without reading it back: s2 (kNil before the first
+    // token), then len (= l2), link, min_endpos (= e2), head, itok, idst
+    uint32_t s2, p_len, p_link, p_endpos, p_head, p_itok, p_idst;
+    uint32_t pad;
 };
 
 // (state, token) -> 32-bit hash; the same function on host and device
@@ -99,11 +110,24 @@ inline uint64_t static_buckets_for(int64_t n_tokens)
     return (slots + kBucketSlots - 1) / kBucketSlots;
 }
 
-inline uint64_t dynamic_buckets_for(int64_t max_seq_len)
+// slots per sequence: at most max_seq_len - 1 are ever used -> load <= 0.5
+inline uint64_t dynamic_slots_for(int64_t max_seq_len)
 {
-    // <= 3T transitions in the worst case -> load <= 0.75
-    uint64_t slots = (uint64_t)max_seq_len * 4 + 64;
-    return (slots + kBucketSlots - 1) / kBucketSlots;
+    return (((uint64_t)max_seq_len * 2 + 64) + 15) / 16 * 16;
 }
+
+constexpr int64_t kCompactMaxSeqLen = 16366;     // 2T+2 state ids below 0x7FFF
+constexpr int32_t kCompactMaxVocab  = 1 << 17;
+
+struct DynRecCompact {   // 16 B
+    uint16_t len, link, endpos, head;   // 0xFFFF = none (link of the root, empty head)
+    uint32_t itok;                      // kNil = no inline transition
+    uint16_t idst, pad;
+};
+
+struct SlotCompact {     // 8 B
+    uint32_t key;        // state << 17 | token, kNil = empty
+    uint16_t dst, next;  // next: 0xFFFF = end of the state's list
+};
 
 }  // namespace sam

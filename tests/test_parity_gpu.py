@@ -63,6 +63,53 @@ def test_dynamic_only(seed, vocab):
     assert_same(g, r, has_static=False)
 
 
+@pytest.mark.parametrize("seed,vocab", [(30, 2), (31, 3), (32, 50)])
+def test_wide_layout_forced(seed, vocab):
+    """The 32-bit table layout (used for long sequences) on the same small cases."""
+    from paper_2411_10666_amd import binding as sam
+    B, T, A, L, steps = 11, 300, 6, 9, 40
+    _say("wide layout seed=%d vocab=%d" % (seed, vocab))
+    corpus, prompts, acc, counts = _random_case(seed, vocab, 1500, B, T, A, L, steps)
+    sam.sam_set_layout_override(1)
+    try:
+        g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L)
+    finally:
+        sam.sam_set_layout_override(0)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r)
+
+
+def test_wide_layout_chosen_for_large_vocab():
+    """A vocabulary above 2^17 does not fit the compact slot key."""
+    vocab = 200_000
+    B, T, A, L, steps = 6, 400, 8, 8, 30
+    _say("large vocab -> wide layout")
+    rng = np.random.default_rng(40)
+    corpus, prompts, acc, counts = _random_case(40, 5, 1500, B, T, A, L, steps)
+    # spread the five symbols over the whole vocabulary, top id included
+    remap = np.array([0, 131071, 131072, 199_999, 77], dtype=np.int32)
+    corpus = remap[corpus]; prompts = [remap[p] for p in prompts]; acc = remap[acc]
+    g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r)
+
+
+def test_compact_layout_top_token_ids():
+    """Token ids at the top of the 17-bit range in the compact slot key."""
+    vocab = 131072
+    B, T, A, L, steps = 6, 400, 8, 8, 30
+    _say("compact layout, vocab 2^17")
+    corpus, prompts, acc, counts = _random_case(41, 4, 1500, B, T, A, L, steps)
+    remap = np.array([0, 131071, 65536, 131070], dtype=np.int32)
+    corpus = remap[corpus]; prompts = [remap[p] for p in prompts]; acc = remap[acc]
+    g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r)
+
+
 def test_long_rows_and_wide_drafts():
     """max_accept above one wavefront of tokens and draft_len above 64 lanes."""
     B, T, A, L, steps, vocab = 5, 1500, 150, 200, 8, 3
