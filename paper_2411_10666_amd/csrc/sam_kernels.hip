@@ -261,6 +261,17 @@ struct Probe {
     uint32_t mh, me;
 };
 
+// Home bucket of (p, t) in a sequence's private table.  The tables are small
+// and at most half full, so a short mix is enough; one multiply-high maps the
+// hash onto the bucket count.
+__device__ __forceinline__ uint32_t dyn_bucket(const DynSeq &D, uint32_t p, uint32_t t)
+{
+    uint32_t h = (p * 0x9E3779B1u) ^ (t * 0x85EBCA77u);
+    h ^= h >> 15;
+    h *= 0x2C1B3C6Du;
+    return __umulhi(h, D.n_buckets);
+}
+
 template <class L>
 __device__ __forceinline__ typename L::RawSlot issue_bucket(const DynSeq &D, uint32_t b, int lane)
 {
@@ -309,7 +320,7 @@ __device__ __forceinline__ void rec_and_probe(const DynSeq &D, uint32_t p, uint3
                                               Rec &R, Probe<L> &P)
 {
     const typename L::RawRec raw = L::issue_rec(D.rec, p);
-    P.b = (uint32_t)bucket_of(hash_key(p, t), D.n_buckets);
+    P.b = dyn_bucket(D, p, t);
     P.sl = issue_bucket<L>(D, P.b, lane);
     reduce_bucket<L>(P, p, t);
     R = L::finish_rec(raw);
@@ -345,8 +356,11 @@ __device__ __forceinline__ void dyn_expand(const DynSeq &D, uint32_t t, uint32_t
     const uint32_t last = c.last;
     const bool writer = lane == 0;
 
-    // `last` never has a transition yet: its first one goes inline
-    if (writer) L::store_inline(D.rec, last, t, cur);
+    // `last` has no transition yet and its record has not been written yet:
+    // write it now, with its first transition (t -> cur) inline
+    Rec LR;
+    LR.len = c.n; LR.link = c.P; LR.endpos = c.n; LR.head = kNil; LR.itok = t; LR.idst = cur;
+    if (writer) L::store_rec(D.rec, last, LR);
     c.n_trans++;
     order_memory();
 
@@ -367,7 +381,7 @@ __device__ __forceinline__ void dyn_expand(const DynSeq &D, uint32_t t, uint32_t
         if (c.pf_ok) {
             pr = c.pf;
         } else {
-            pr.b = (uint32_t)bucket_of(hash_key(p, t), D.n_buckets);
+            pr.b = dyn_bucket(D, p, t);
             pr.sl = issue_bucket<L>(D, pr.b, lane);
             reduce_bucket<L>(pr, p, t);
         }
@@ -404,14 +418,14 @@ __device__ __forceinline__ void dyn_expand(const DynSeq &D, uint32_t t, uint32_t
             // q's record, and with it the next token's first lookup (at q)
             const typename L::RawRec rawq = L::issue_rec(D.rec, q);
             if (tn != kNil) {
-                new_pf.b = (uint32_t)bucket_of(hash_key(q, tn), D.n_buckets);
+                new_pf.b = dyn_bucket(D, q, tn);
                 new_pf.sl = issue_bucket<L>(D, new_pf.b, lane);
                 reduce_bucket<L>(new_pf, q, tn);
                 pin_s(new_pf.mh);
             }
             Rec Q = L::finish_rec(rawq);
             pin_s(Q.len);
-            if (q == last) { Q.itok = t; Q.idst = cur; }
+            if (q == last) Q = LR;
             if (R.len + 1 == Q.len) {
                 newP = q;
                 newRP = Q;
@@ -432,7 +446,7 @@ __device__ __forceinline__ void dyn_expand(const DynSeq &D, uint32_t t, uint32_t
                     const uint32_t tok = uni(L::slot_token(sl)), d = uni(L::slot_dst(sl));
                     j = uni(L::slot_next(sl));
                     Probe<L> pc;
-                    pc.b = (uint32_t)bucket_of(hash_key(cl, tok), D.n_buckets);
+                    pc.b = dyn_bucket(D, cl, tok);
                     pc.sl = issue_bucket<L>(D, pc.b, lane);
                     reduce_bucket<L>(pc, cl, tok);
                     uint32_t at, dummy;
@@ -471,14 +485,17 @@ __device__ __forceinline__ void dyn_expand(const DynSeq &D, uint32_t t, uint32_t
             }
         }
     }
-    if (writer) {
-        Rec C;
-        C.len = k; C.link = newP; C.endpos = k; C.head = kNil; C.itok = kNil; C.idst = 0;
-        L::store_rec(D.rec, cur, C);
-        D.text[c.n] = (int32_t)t;
-    }
-    order_memory();
+    // the record of `cur` is written by the next call (or by flush_last)
     c.n = k; c.last = cur; c.P = newP; c.RP = newRP; c.pf_ok = new_pf_ok; c.pf = new_pf;
+}
+
+// Write the record of `last` (no transition yet) at the end of a launch.
+template <class L>
+__device__ __forceinline__ void flush_last(const DynSeq &D, const DynCursor<L> &c, int lane)
+{
+    Rec LR;
+    LR.len = c.n; LR.link = c.P; LR.endpos = c.n; LR.head = kNil; LR.itok = kNil; LR.idst = 0;
+    if (lane == 0) L::store_rec(D.rec, c.last, LR);
 }
 
 }  // namespace
@@ -559,17 +576,22 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
             const int m = (int)((count - base) < 64 ? (count - base) : 64);
             const uint32_t tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
             c.pf_ok = false;
-            for (int i = 0; i < m; i++) {
-                const uint32_t t = lane_get(tv, i);
+            const uint32_t n_chunk = c.n;
+            int fed = 0;
+            for (; fed < m; fed++) {
+                const uint32_t t = lane_get(tv, fed);
                 if (t >= vocab) { stop = true; fault |= SAM_STATUS_TOKEN_BIT; break; }
                 uint32_t tn = kNil;
-                if (i + 1 < m) {
-                    tn = lane_get(tv, i + 1);
+                if (fed + 1 < m) {
+                    tn = lane_get(tv, fed + 1);
                     if (tn >= vocab) tn = kNil;
                 }
                 dyn_expand<L>(D, t, tn, lane, c, fault);
             }
+            // the sequence's text, one coalesced store per chunk
+            if (lane < fed) D.text[n_chunk + lane] = (int32_t)tv;
         }
+        if (c.n != n0) flush_last<L>(D, c, lane);
         if (lane == 0) {
             sh[3] = c.P == kNil ? 0u : c.RP.len;
             sh[4] = c.P == kNil ? 0u : c.RP.endpos;
