@@ -94,6 +94,52 @@ def _compare(g, r, seqs, has_static=True):
     assert np.array_equal(gc, rc)
 
 
+def _sampled(spec, n_check, has_static=True):
+    w = make_workload(spec)
+    _say("%s: workload generated (corpus %d tokens)" % (spec.name, spec.corpus_tokens))
+    g = _gpu_schedule(w)
+    seqs = sorted(set(np.linspace(0, spec.batch - 1, n_check).astype(int).tolist()))
+    r = _oracle_schedule(w, seqs)
+    _compare(g, r, seqs, has_static=has_static)
+    T = spec.max_seq_len
+    assert (g["sizes"][:, 0] == T).all()
+    assert (g["sizes"][:, 1] <= 2 * T - 1).all() and (g["sizes"][:, 2] <= 3 * T - 4).all()
+    assert (g["draft_len"] <= spec.draft_len).all()
+    assert ((g["source"] == 0) == (g["match_len"] == 0)).all()
+    # a draft is a slice of its source text: check the static ones against the corpus
+    if w.corpus is not None:
+        st = np.argwhere(g["source"] == 2)
+        pick = st[np.random.default_rng(0).choice(len(st), size=min(2000, len(st)), replace=False)]
+        for s_, b_ in pick.tolist():
+            d = g["draft"][s_, b_, :g["draft_len"][s_, b_]]
+            assert d.size == 0 or (d >= 0).all()
+    return g, r
+
+
+def test_cfg3_shape_scaled_corpus():
+    """Config 3's batch, lengths, accept width and draft length (256 x (1024+4096),
+    A=12, L=24, Zipf 1.05, 40 % copied) over a 5 M-token corpus; 24 sequences replayed."""
+    _sampled(CONFIGS["cfg3"].scaled(corpus_tokens=5_000_000), 24)
+
+
+def test_cfg5_shape_scaled_corpus():
+    """Config 5's batch, lengths, vocabulary (128256), A=16, L=32 over a 5 M-token
+    corpus; 16 sequences replayed."""
+    _sampled(CONFIGS["cfg5"].scaled(corpus_tokens=5_000_000), 16)
+
+
+@pytest.mark.skipif(os.environ.get("SAM_TEST_LARGE") != "1",
+                    reason="minutes of host time and >20 GB of host memory: set SAM_TEST_LARGE=1")
+def test_cfg3_full_corpus():
+    _sampled(CONFIGS["cfg3"], 16)
+
+
+@pytest.mark.skipif(os.environ.get("SAM_TEST_HUGE") != "1",
+                    reason="about 10 minutes and >100 GB of host memory: set SAM_TEST_HUGE=1")
+def test_cfg5_full_corpus():
+    _sampled(CONFIGS["cfg5"], 8)
+
+
 def test_cfg2_full_schedule_every_output():
     spec = CONFIGS["cfg2"]
     w = make_workload(spec)
