@@ -159,6 +159,24 @@ int sam_batch_step(sam_batch *batch, const int32_t *accepted, const int32_t *cou
                    int32_t *source, void *hip_stream);
 
 /*
+ * Recycle sequences of a live batch for new requests (continuous batching): each
+ * listed sequence is forgotten (its dynamic automaton emptied, its static cursor
+ * back at the root) and the new prompt is ingested exactly as sam_batch_init
+ * does.  Other sequences are not touched.
+ *   slots          : device, int32 [n_slots], distinct sequence indices in
+ *                    [0, batch).
+ *   prompt_tokens  : device, int32, the new prompts concatenated.
+ *   prompt_offsets : device, int64 [n_slots+1]; prompt i (for sequence slots[i])
+ *                    is prompt_tokens[offsets[i] : offsets[i+1]).
+ * Reads slots and offsets back to validate them (synchronises the stream), then
+ * enqueues the work and returns.  A bad prompt token raises SAM_STATUS_TOKEN.
+ * Errors: SAM_EINVAL, SAM_ECAPACITY, SAM_ENOMEM, SAM_EDEVICE.
+ */
+int sam_batch_reset(sam_batch *batch, const int32_t *slots, int32_t n_slots,
+                    const int32_t *prompt_tokens, const int64_t *prompt_offsets,
+                    void *hip_stream);
+
+/*
  * Both cursors of every sequence, for checking: static (s1, l1) and dynamic
  * (s2, l2), each device int32 [batch]; any may be NULL.  The dynamic cursor is
  * the state holding the longest suffix of the sequence that also ends earlier

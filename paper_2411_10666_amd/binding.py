@@ -24,6 +24,7 @@ EXPORTS = [
     "sam_corpus_export", "sam_corpus_find", "sam_corpus_free", "sam_batch_init",
     "sam_batch_step", "sam_batch_debug", "sam_batch_sizes", "sam_batch_status",
     "sam_batch_info", "sam_batch_free", "sam_set_layout_override",
+    "sam_batch_reset",
 ]
 
 
@@ -50,6 +51,7 @@ def _load():
     L.sam_corpus_free.restype = None
     L.sam_batch_init.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, C.POINTER(vp)]
     L.sam_batch_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+    L.sam_batch_reset.argtypes = [vp, vp, i32, vp, vp, vp]
     L.sam_batch_debug.argtypes = [vp, vp, vp, vp, vp, vp]
     L.sam_batch_sizes.argtypes = [vp, vp, vp, vp, vp]
     L.sam_batch_status.argtypes = [vp, C.POINTER(C.c_uint32), vp]
@@ -191,6 +193,15 @@ def sam_batch_step(batch: Batch, accepted, counts, match_len, draft, draft_len, 
                                _dev_ptr(draft, i32, "draft"),
                                _dev_ptr(draft_len, i32, "draft_len"),
                                _dev_ptr(source, i32, "source"), _stream_ptr(stream)))
+
+
+def sam_batch_reset(batch: Batch, slots, prompt_tokens, prompt_offsets, stream=None) -> None:
+    import torch
+    _check(_lib.sam_batch_reset(batch._h, _dev_ptr(slots, torch.int32, "slots"),
+                                int(slots.numel()),
+                                _dev_ptr(prompt_tokens, torch.int32, "prompt_tokens"),
+                                _dev_ptr(prompt_offsets, torch.int64, "prompt_offsets"),
+                                _stream_ptr(stream)))
 
 
 class StepPlan:

@@ -270,9 +270,9 @@ int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
     bt->device_bytes = (int64_t)(b_text + b_rec + b_slots + b_meta + 256);
     StaticView S = corpus ? corpus->view : StaticView{};
     if ((e = hipMemsetAsync(v.dyn_slots, 0xFF, b_slots, stream)) != hipSuccess ||
-        (e = launch_reset(v, stream)) != hipSuccess ||
-        (e = launch_feed(S, v, prompt_tokens, prompt_offsets, nullptr, nullptr, nullptr, nullptr,
-                         nullptr, stream)) != hipSuccess ||
+        (e = launch_reset(v, nullptr, batch, stream)) != hipSuccess ||
+        (e = launch_feed(S, v, nullptr, batch, prompt_tokens, prompt_offsets, nullptr, nullptr,
+                         nullptr, nullptr, nullptr, stream)) != hipSuccess ||
         (e = hipStreamSynchronize(stream)) != hipSuccess) {
         batch_release(bt);
         return fail_hip("sam_batch_init: prompt ingest", e);
@@ -298,9 +298,59 @@ int sam_batch_step(sam_batch *bt, const int32_t *accepted, const int32_t *counts
     if (!accepted || !counts || !match_len || !draft || !draft_len || !source)
         return fail(SAM_EINVAL, "sam_batch_step: NULL buffer");
     StaticView S = bt->corpus ? bt->corpus->view : StaticView{};
-    hipError_t e = launch_feed(S, bt->view, accepted, nullptr, counts, match_len, draft,
-                               draft_len, source, (hipStream_t)hip_stream);
+    hipError_t e = launch_feed(S, bt->view, nullptr, bt->view.batch, accepted, nullptr, counts,
+                               match_len, draft, draft_len, source, (hipStream_t)hip_stream);
     if (e != hipSuccess) return fail_hip("sam_batch_step: launch", e);
+    return SAM_OK;
+}
+
+int sam_batch_reset(sam_batch *bt, const int32_t *slots, int32_t n_slots,
+                    const int32_t *prompt_tokens, const int64_t *prompt_offsets, void *hip_stream)
+{
+    if (!bt) return fail(SAM_EINVAL, "sam_batch_reset: batch is NULL");
+    if (!slots || !prompt_tokens || !prompt_offsets)
+        return fail(SAM_EINVAL, "sam_batch_reset: NULL buffer");
+    const BatchView &v = bt->view;
+    if (n_slots < 1 || n_slots > v.batch)
+        return fail(SAM_EINVAL, "sam_batch_reset: n_slots must be in 1 .. batch");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    std::vector<int32_t> hs;
+    std::vector<int64_t> offs;
+    std::vector<char> seen;
+    try {
+        hs.resize((size_t)n_slots);
+        offs.resize((size_t)n_slots + 1);
+        seen.assign((size_t)v.batch, 0);
+    } catch (const std::bad_alloc &) {
+        return fail(SAM_ENOMEM, "sam_batch_reset: out of host memory");
+    }
+    HIP_TRY(hipMemcpyAsync(hs.data(), slots, hs.size() * sizeof(int32_t), hipMemcpyDeviceToHost,
+                           stream));
+    HIP_TRY(hipMemcpyAsync(offs.data(), prompt_offsets, offs.size() * sizeof(int64_t),
+                           hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    if (offs[0] < 0) return fail(SAM_EINVAL, "sam_batch_reset: prompt_offsets[0] < 0");
+    for (int32_t i = 0; i < n_slots; i++) {
+        if (hs[i] < 0 || hs[i] >= v.batch)
+            return fail(SAM_EINVAL, "sam_batch_reset: slot " + std::to_string(hs[i]) +
+                                        " is outside the batch");
+        if (seen[hs[i]])
+            return fail(SAM_EINVAL, "sam_batch_reset: slot " + std::to_string(hs[i]) +
+                                        " is listed twice");
+        seen[hs[i]] = 1;
+        const int64_t len = offs[i + 1] - offs[i];
+        if (len < 0) return fail(SAM_EINVAL, "sam_batch_reset: prompt_offsets must not decrease");
+        if (len > (int64_t)v.max_seq_len)
+            return fail(SAM_ECAPACITY, "sam_batch_reset: prompt " + std::to_string(i) + " has " +
+                                           std::to_string(len) + " tokens, max_seq_len is " +
+                                           std::to_string(v.max_seq_len));
+    }
+    StaticView S = bt->corpus ? bt->corpus->view : StaticView{};
+    hipError_t e;
+    if ((e = launch_reset(v, slots, n_slots, stream)) != hipSuccess ||
+        (e = launch_feed(S, v, slots, n_slots, prompt_tokens, prompt_offsets, nullptr, nullptr,
+                         nullptr, nullptr, nullptr, stream)) != hipSuccess)
+        return fail_hip("sam_batch_reset: launch", e);
     return SAM_OK;
 }
 

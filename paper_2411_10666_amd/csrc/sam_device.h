@@ -42,10 +42,16 @@ struct BatchView {
     uint32_t *status;          // [1]
 };
 
-hipError_t launch_feed(const StaticView &S, const BatchView &B, const int32_t *tokens,
-                       const int64_t *offsets, const int32_t *counts, int32_t *match_len,
-                       int32_t *draft, int32_t *draft_len, int32_t *source, hipStream_t stream);
-hipError_t launch_reset(const BatchView &B, hipStream_t stream);
+// seq_map (device, may be NULL): in ingest mode workgroup i serves sequence seq_map[i];
+// n_seqs workgroups are launched.  Step mode always covers the whole batch.
+hipError_t launch_feed(const StaticView &S, const BatchView &B, const int32_t *seq_map,
+                       int n_seqs, const int32_t *tokens, const int64_t *offsets,
+                       const int32_t *counts, int32_t *match_len, int32_t *draft,
+                       int32_t *draft_len, int32_t *source, hipStream_t stream);
+// seq_map NULL: fresh records and cursors for sequences 0 .. n_seqs-1 (slot tables
+// are cleared by the caller).  Otherwise: the listed sequences, slot tables included.
+hipError_t launch_reset(const BatchView &B, const int32_t *seq_map, int n_seqs,
+                        hipStream_t stream);
 hipError_t launch_debug(const BatchView &B, int32_t *s1, int32_t *l1, int32_t *s2, int32_t *l2,
                         int32_t *text_len, int32_t *n_states, int32_t *n_trans,
                         hipStream_t stream);

@@ -506,6 +506,7 @@ __device__ __forceinline__ void flush_last(const DynSeq &D, const DynCursor<L> &
 // tokens[b * max_accept ...], then source selection and draft gather.
 template <class L, bool kIngest>
 __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B,
+                                                        const int32_t *__restrict__ seq_map,
                                                         const int32_t *__restrict__ tokens,
                                                         const int64_t *__restrict__ offsets,
                                                         const int32_t *__restrict__ counts,
@@ -515,7 +516,8 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
                                                         int32_t *__restrict__ source)
 {
     __shared__ uint32_t sh[8];
-    const int b = blockIdx.x;
+    // ingest may address a subset of the batch: workgroup i serves sequence seq_map[i]
+    const int b = (kIngest && seq_map) ? seq_map[blockIdx.x] : (int)blockIdx.x;
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
 
@@ -527,7 +529,7 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
     int64_t count;
     uint32_t fault = 0;
     if (kIngest) {
-        const int64_t o0 = offsets[b], o1 = offsets[b + 1];
+        const int64_t o0 = offsets[blockIdx.x], o1 = offsets[blockIdx.x + 1];
         tok = tokens + o0;
         count = o1 - o0;
     } else {
@@ -642,10 +644,11 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
 
 // Fresh sequences: root record, empty cursors.  The slot tables are filled with
 // the empty key by the caller.
-__global__ void sam_reset_kernel(BatchView B)
+__global__ void sam_reset_kernel(BatchView B, const int32_t *seq_map, int n)
 {
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= B.batch) return;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int b = seq_map ? seq_map[i] : i;
     Rec r;
     r.len = 0; r.link = kNil; r.endpos = 0; r.head = kNil; r.itok = kNil; r.idst = 0;
     if (B.compact) {
@@ -662,7 +665,19 @@ __global__ void sam_reset_kernel(BatchView B)
     m.s2 = kNil;
     m.p_link = kNil; m.p_head = kNil; m.p_itok = kNil;
     B.meta[b] = m;
-    if (b == 0) *B.status = 0;
+    if (!seq_map && b == 0) *B.status = 0;
+}
+
+// Empty the slot tables of the listed sequences (every key = kNil).
+__global__ void sam_clear_slots_kernel(BatchView B, const int32_t *seq_map)
+{
+    const int b = seq_map[blockIdx.x];
+    uint4 *base = reinterpret_cast<uint4 *>(reinterpret_cast<char *>(B.dyn_slots) +
+                                           (size_t)b * B.dyn_buckets * 128);
+    const size_t n16 = (size_t)B.dyn_buckets * 8;
+    for (size_t i = (size_t)blockIdx.y * blockDim.x + threadIdx.x; i < n16;
+         i += (size_t)gridDim.y * blockDim.x)
+        base[i] = make_uint4(kNil, kNil, kNil, kNil);
 }
 
 __global__ void sam_debug_kernel(BatchView B, int32_t *s1, int32_t *l1, int32_t *s2, int32_t *l2,
@@ -682,32 +697,45 @@ __global__ void sam_debug_kernel(BatchView B, int32_t *s1, int32_t *l1, int32_t 
 
 // ---- launchers (called from the C ABI) ------------------------------------
 
-hipError_t launch_feed(const StaticView &S, const BatchView &B, const int32_t *tokens,
-                       const int64_t *offsets, const int32_t *counts, int32_t *match_len,
-                       int32_t *draft, int32_t *draft_len, int32_t *source, hipStream_t stream)
+hipError_t launch_feed(const StaticView &S, const BatchView &B, const int32_t *seq_map,
+                       int n_seqs, const int32_t *tokens, const int64_t *offsets,
+                       const int32_t *counts, int32_t *match_len, int32_t *draft,
+                       int32_t *draft_len, int32_t *source, hipStream_t stream)
 {
-    const dim3 grid(B.batch), block(128);
+    const dim3 grid(n_seqs), block(128);
     if (offsets) {
         if (B.compact)
             hipLaunchKernelGGL((sam_feed_kernel<CompactDyn, true>), grid, block, 0, stream, S, B,
-                               tokens, offsets, counts, match_len, draft, draft_len, source);
+                               seq_map, tokens, offsets, counts, match_len, draft, draft_len,
+                               source);
         else
             hipLaunchKernelGGL((sam_feed_kernel<WideDyn, true>), grid, block, 0, stream, S, B,
-                               tokens, offsets, counts, match_len, draft, draft_len, source);
+                               seq_map, tokens, offsets, counts, match_len, draft, draft_len,
+                               source);
     } else {
         if (B.compact)
             hipLaunchKernelGGL((sam_feed_kernel<CompactDyn, false>), grid, block, 0, stream, S, B,
-                               tokens, offsets, counts, match_len, draft, draft_len, source);
+                               seq_map, tokens, offsets, counts, match_len, draft, draft_len,
+                               source);
         else
             hipLaunchKernelGGL((sam_feed_kernel<WideDyn, false>), grid, block, 0, stream, S, B,
-                               tokens, offsets, counts, match_len, draft, draft_len, source);
+                               seq_map, tokens, offsets, counts, match_len, draft, draft_len,
+                               source);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_reset(const BatchView &B, hipStream_t stream)
+hipError_t launch_reset(const BatchView &B, const int32_t *seq_map, int n_seqs,
+                        hipStream_t stream)
 {
-    hipLaunchKernelGGL(sam_reset_kernel, dim3((B.batch + 127) / 128), dim3(128), 0, stream, B);
+    if (seq_map) {
+        hipLaunchKernelGGL(sam_clear_slots_kernel, dim3(n_seqs, 16), dim3(256), 0, stream, B,
+                           seq_map);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(sam_reset_kernel, dim3((n_seqs + 127) / 128), dim3(128), 0, stream, B,
+                       seq_map, n_seqs);
     return hipGetLastError();
 }
 

@@ -201,6 +201,78 @@ def test_device_side_faults_leave_other_sequences_intact():
     assert_same(g, r)
 
 
+def test_reset_recycles_sequences():
+    """Continuous batching: some sequences are replaced by new requests in the
+    middle of a run; the others carry on untouched."""
+    import torch
+    from oracle.sam_oracle import Sam, Sequence
+    from paper_2411_10666_amd import binding as sam
+    dev = torch.device("cuda:0")
+    vocab, T, A, L, B = 4, 200, 5, 6, 7
+    rng = np.random.default_rng(77)
+    corpus = rng.integers(0, vocab, size=1500).astype(np.int32)
+    st = Sam.build(corpus)
+    gc = sam.sam_build(corpus, vocab)
+    prompts = [rng.integers(0, vocab, size=int(rng.integers(0, 40))).astype(np.int32) for _ in range(B)]
+    offs = np.zeros(B + 1, np.int64); offs[1:] = np.cumsum([len(p) for p in prompts])
+    batch = sam.sam_batch_init(gc, torch.from_numpy(np.concatenate(prompts)).to(dev),
+                               torch.from_numpy(offs).to(dev), B, vocab, T, A, L)
+    seqs = [Sequence(st, corpus) for _ in range(B)]
+    for q, p in zip(seqs, prompts):
+        q.feed(p)
+    i32 = dict(dtype=torch.int32, device=dev)
+    ml = torch.empty(B, **i32); dl = torch.empty(B, **i32); src = torch.empty(B, **i32)
+    dr = torch.empty(B, L, **i32)
+    cur = [torch.empty(B, **i32) for _ in range(4)]
+    siz = [torch.empty(B, **i32) for _ in range(3)]
+    used = np.array([len(p) for p in prompts])
+    _say("reset / recycle sequences")
+    for step in range(60):
+        if step in (10, 25, 40):
+            pick = sorted(rng.choice(B, size=int(rng.integers(1, 4)), replace=False).tolist())
+            newp = [rng.integers(0, vocab, size=int(rng.integers(0, 50))).astype(np.int32) for _ in pick]
+            no = np.zeros(len(pick) + 1, np.int64); no[1:] = np.cumsum([len(p) for p in newp])
+            flat = np.concatenate(newp) if no[-1] else np.zeros(1, np.int32)
+            sam.sam_batch_reset(batch, torch.tensor(pick, **i32), torch.from_numpy(flat).to(dev),
+                                torch.from_numpy(no).to(dev))
+            for b, p in zip(pick, newp):
+                seqs[b] = Sequence(st, corpus)
+                seqs[b].feed(p)
+                used[b] = len(p)
+        c = np.minimum(rng.integers(0, A + 1, size=B), T - used)
+        used += c
+        acc = rng.integers(0, vocab, size=(B, A)).astype(np.int32)
+        sam.sam_batch_step(batch, torch.from_numpy(acc).to(dev), torch.from_numpy(c.astype(np.int32)).to(dev),
+                           ml, dr, dl, src)
+        sam.sam_batch_debug(batch, *cur)
+        sam.sam_batch_sizes(batch, *siz)
+        torch.cuda.synchronize()
+        for b in range(B):
+            seqs[b].feed(acc[b, :c[b]])
+            r = seqs[b].draft(L, 0)
+            got = (int(ml[b]), int(src[b]), int(dl[b]))
+            assert got == (r["match_len"], r["source"], r["draft_len"]), (step, b)
+            assert (dr[b].cpu().numpy() == r["draft"]).all(), (step, b)
+            assert tuple(int(x[b]) for x in cur) == seqs[b].cursors(), (step, b)
+            dyn = seqs[b].dynamic()
+            assert (int(siz[0][b]), int(siz[1][b]), int(siz[2][b])) == (used[b], dyn.num_states, dyn.num_trans)
+    assert sam.sam_batch_status(batch) == 0
+    # argument errors
+    two = torch.tensor([1, 1], **i32)
+    o3 = torch.tensor([0, 1, 2], dtype=torch.int64, device=dev)
+    tok = torch.zeros(4, **i32)
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_batch_reset(batch, two, tok, o3)
+    assert e.value.code == sam.SAM_EINVAL and "twice" in str(e.value)
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_batch_reset(batch, torch.tensor([B], **i32), tok, o3[:2].contiguous())
+    assert e.value.code == sam.SAM_EINVAL
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_batch_reset(batch, torch.tensor([0], **i32), torch.zeros(T + 5, **i32),
+                            torch.tensor([0, T + 1], dtype=torch.int64, device=dev))
+    assert e.value.code == sam.SAM_ECAPACITY
+
+
 def test_init_errors():
     import torch
     from paper_2411_10666_amd import binding as sam
