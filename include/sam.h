@@ -82,6 +82,15 @@ int sam_build(const int32_t *corpus_tokens, int64_t n_tokens, int32_t vocab,
               sam_corpus **out);
 
 /*
+ * Progress reports from sam_build / sam_build_host_only, for corpora that take
+ * minutes: `fn` (NULL to switch off) is called on the building thread about every
+ * 16 M tokens with phase "build", then during "finalize" and before "upload".
+ * Process-wide; set it before the build call.
+ */
+typedef void (*sam_progress_fn)(const char *phase, int64_t done, int64_t total, void *user);
+int sam_set_progress_callback(sam_progress_fn fn, void *user);
+
+/*
  * Same host construction as sam_build but nothing is copied to a device, so it
  * runs on a machine without a GPU.  The handle can be inspected
  * (sam_corpus_info / _export / _find) but not used by sam_batch_init.

@@ -221,6 +221,14 @@ osam *osam_build(const int32_t *tokens, int64_t n)
     return S;
 }
 
+/* Expand by a run of tokens (Build-SAM's loop, resumable) */
+int osam_extend(osam *S, const int32_t *tokens, int64_t n)
+{
+    for (int64_t i = 0; i < n; i++)
+        if (osam_expand(S, tokens[i]) != 0) return -1;
+    return 0;
+}
+
 /* ---- Transfer (Algorithm 1) -------------------------------------------- */
 
 void osam_transfer(const osam *S, int32_t t, int32_t *s_io, int32_t *l_io, owalk *w)

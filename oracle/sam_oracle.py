@@ -52,6 +52,8 @@ def lib():
             L.osam_free.argtypes = [C.c_void_p]
             L.osam_expand.argtypes = [C.c_void_p, C.c_int32]
             L.osam_expand.restype = C.c_int
+            L.osam_extend.argtypes = [C.c_void_p, _i32p, C.c_int64]
+            L.osam_extend.restype = C.c_int
             L.osam_build.argtypes = [_i32p, C.c_int64]
             L.osam_build.restype = C.c_void_p
             L.osam_transfer.argtypes = [C.c_void_p, C.c_int32, _i32p, _i32p, C.c_void_p]
@@ -97,12 +99,22 @@ class Sam:
             raise MemoryError("osam_new failed")
 
     @classmethod
-    def build(cls, tokens) -> "Sam":
+    def build(cls, tokens, progress=None, chunk=1 << 24) -> "Sam":
+        """Build-SAM.  With `progress` (a callable taking done, total) the tokens
+        are fed in chunks and it is called between them."""
         t = np.ascontiguousarray(tokens, dtype=np.int32)
-        h = lib().osam_build(_p32(t), len(t))
-        if not h:
-            raise MemoryError("osam_build failed")
-        return cls(h)
+        if progress is None:
+            h = lib().osam_build(_p32(t), len(t))
+            if not h:
+                raise MemoryError("osam_build failed")
+            return cls(h)
+        S = cls()
+        for lo in range(0, len(t), chunk):
+            progress(lo, len(t))
+            part = t[lo:lo + chunk]
+            if S._L.osam_extend(S._h, _p32(part), len(part)) != 0:
+                raise MemoryError("osam_extend failed")
+        return S
 
     def __del__(self):
         if getattr(self, "_owned", False) and getattr(self, "_h", None):

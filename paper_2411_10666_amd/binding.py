@@ -24,8 +24,11 @@ EXPORTS = [
     "sam_corpus_export", "sam_corpus_find", "sam_corpus_free", "sam_batch_init",
     "sam_batch_step", "sam_batch_debug", "sam_batch_sizes", "sam_batch_status",
     "sam_batch_info", "sam_batch_free", "sam_set_layout_override",
-    "sam_batch_reset",
+    "sam_batch_reset", "sam_set_progress_callback",
 ]
+
+
+PROGRESS_FN = C.CFUNCTYPE(None, C.c_char_p, C.c_int64, C.c_int64, C.c_void_p)
 
 
 class SamError(RuntimeError):
@@ -51,6 +54,7 @@ def _load():
     L.sam_corpus_free.restype = None
     L.sam_batch_init.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, C.POINTER(vp)]
     L.sam_batch_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+    L.sam_set_progress_callback.argtypes = [PROGRESS_FN, vp]
     L.sam_batch_reset.argtypes = [vp, vp, i32, vp, vp, vp]
     L.sam_batch_debug.argtypes = [vp, vp, vp, vp, vp, vp]
     L.sam_batch_sizes.argtypes = [vp, vp, vp, vp, vp]
@@ -261,6 +265,21 @@ def sam_batch_status(batch: Batch, stream=None) -> int:
     st = C.c_uint32()
     _check(_lib.sam_batch_status(batch._h, C.byref(st), _stream_ptr(stream)))
     return st.value
+
+
+_progress_keep = None
+
+
+def sam_set_progress_callback(fn) -> None:
+    """fn(phase: str, done: int, total: int) or None."""
+    global _progress_keep
+    if fn is None:
+        _progress_keep = None
+        _check(_lib.sam_set_progress_callback(PROGRESS_FN(), None))
+        return
+    cb = PROGRESS_FN(lambda phase, done, total, user: fn(phase.decode(), done, total))
+    _progress_keep = cb
+    _check(_lib.sam_set_progress_callback(cb, None))
 
 
 def sam_set_layout_override(mode: int) -> None:

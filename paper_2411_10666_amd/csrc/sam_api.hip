@@ -20,6 +20,8 @@ namespace {
 
 thread_local std::string g_err;
 int g_layout_override = 0;   // 0: pick per batch, 1: always the wide layout
+HostSam::ProgressFn g_progress = nullptr;
+void *g_progress_user = nullptr;
 
 int fail(int code, const std::string &msg)
 {
@@ -113,7 +115,7 @@ static int build_common(const int32_t *tokens, int64_t n, int32_t vocab, bool up
     std::string err;
     int rc;
     try {
-        rc = c->host.build(tokens, n, vocab, err);
+        rc = c->host.build(tokens, n, vocab, err, g_progress, g_progress_user);
     } catch (const std::bad_alloc &) {
         rc = SAM_ENOMEM;
         err = "sam_build: out of host memory";
@@ -123,6 +125,7 @@ static int build_common(const int32_t *tokens, int64_t n, int32_t vocab, bool up
         return fail(rc, err);
     }
     if (upload) {
+        if (g_progress) g_progress("upload", 0, 1, g_progress_user);
         rc = corpus_upload(c);
         if (rc != SAM_OK) {
             corpus_release_device(c);
@@ -381,6 +384,13 @@ int sam_batch_status(const sam_batch *bt, uint32_t *status, void *hip_stream)
     HIP_TRY(hipMemcpyAsync(status, bt->view.status, sizeof(uint32_t), hipMemcpyDeviceToHost,
                            stream));
     HIP_TRY(hipStreamSynchronize(stream));
+    return SAM_OK;
+}
+
+int sam_set_progress_callback(sam_progress_fn fn, void *user)
+{
+    g_progress = fn;
+    g_progress_user = user;
     return SAM_OK;
 }
 

@@ -42,7 +42,8 @@ inline uint64_t probe(const Slot *slots, uint64_t n_buckets, uint32_t state, uin
 
 }  // namespace
 
-int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string &err)
+int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string &err,
+                   ProgressFn progress, void *user)
 {
     if (!tokens || n < 1 || n > 0x7FFFFFFELL || vocab_ < 1) {
         err = "sam_build: need tokens != NULL, 1 <= n_tokens <= 2^31-2, vocab >= 1";
@@ -98,6 +99,7 @@ int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string
     uint32_t last = 0;
 
     for (int64_t i = 0; i < n; i++) {
+        if (progress && (i & ((1 << 24) - 1)) == 0) progress("build", i, n, user);
         const uint32_t t = (uint32_t)tokens[i];
         const uint32_t c = new_state((uint32_t)(i + 1), 0, (uint32_t)(i + 1));
         uint32_t p = last;
@@ -150,8 +152,11 @@ int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string
     }
 
     // the device reads min_endpos(target) where the build kept the list chain
-    for (uint64_t j = 0; j < n_slots; j++)
+    for (uint64_t j = 0; j < n_slots; j++) {
+        if (progress && (j & ((1ull << 27) - 1)) == 0)
+            progress("finalize", (int64_t)j, (int64_t)n_slots, user);
         if (slots[j].state != kNil) slots[j].w = endpos[slots[j].dst];
+    }
     for (int32_t t = 0; t < vocab; t++)
         if (root[t].dst) root[t].endpos = endpos[root[t].dst];
     std::vector<uint32_t>().swap(head);

@@ -27,8 +27,11 @@ struct HostSam {
     HostSam(const HostSam &) = delete;
     HostSam &operator=(const HostSam &) = delete;
 
-    // returns SAM_OK or an error code; message in err
-    int build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string &err);
+    // returns SAM_OK or an error code; message in err.  `progress` (may be
+    // null) is called now and then with a phase name and done/total counts.
+    typedef void (*ProgressFn)(const char *phase, int64_t done, int64_t total, void *user);
+    int build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string &err,
+              ProgressFn progress = nullptr, void *user = nullptr);
 
     // next(state)[token] or kNil
     uint32_t find(uint32_t state, uint32_t token) const;

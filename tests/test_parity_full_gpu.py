@@ -33,7 +33,12 @@ def _gpu_schedule(w, sequences=None):
     spec = w.spec
     dev = torch.device("cuda:0")
     t0 = time.time()
-    corpus = sam.sam_build(w.corpus, spec.vocab) if w.corpus is not None else None
+    sam.sam_set_progress_callback(
+        lambda phase, done, total: _say("%s: library %s %d/%d" % (spec.name, phase, done, total)))
+    try:
+        corpus = sam.sam_build(w.corpus, spec.vocab) if w.corpus is not None else None
+    finally:
+        sam.sam_set_progress_callback(None)
     _say("%s: library built the corpus automaton in %.1f s" % (spec.name, time.time() - t0))
     B, A, L, S = spec.batch, spec.max_accept, spec.draft_len, w.steps
     i32 = dict(dtype=torch.int32, device=dev)
@@ -64,7 +69,10 @@ def _oracle_schedule(w, seqs):
     from oracle.sam_oracle import Batch, Sam
     spec = w.spec
     t0 = time.time()
-    static = Sam.build(w.corpus) if w.corpus is not None else None
+    static = None
+    if w.corpus is not None:
+        static = Sam.build(w.corpus, progress=lambda done, total: _say(
+            "%s: checker build %d/%d" % (spec.name, done, total)))
     _say("%s: checker built the corpus automaton in %.1f s" % (spec.name, time.time() - t0))
     ob = Batch(static, w.corpus, [w.prompts[b] for b in seqs], spec.max_accept, spec.draft_len,
                spec.l_bias)
