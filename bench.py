@@ -44,6 +44,32 @@ ALGO_BYTES_PER_MATCH_STEP = {
 }
 
 
+# HBM bytes per step launch of sam_feed_kernel from rocprofv3 counter runs
+# (FETCH_SIZE and WRITE_SIZE, each scaled by the same counter's reading for a copy
+# kernel of known size), with the digest of the kernel sources they were taken
+# on: the figure is reported only while those sources are unchanged.
+MEASURED_TRAFFIC = {
+}
+
+KERNEL_SOURCES = ["sam_kernels.hip", "sam_layout.h", "sam_device.h"]
+
+
+def kernel_sources_digest():
+    import hashlib
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2411_10666_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(name):
+    m = MEASURED_TRAFFIC.get(name)
+    if not m or m["sources"] != kernel_sources_digest():
+        return None
+    return m["bytes_per_launch"]
+
+
 def _log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
@@ -175,6 +201,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", default="cfg2", choices=sorted(CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB before the timed "
+                         "steps (a kernel of known traffic to scale profiler counters by)")
+
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (sequences are independent and "
@@ -190,6 +220,17 @@ def main():
     _log("%s: corpus %d tokens, batch %d, %d+%d tokens per sequence, %d steps in the schedule "
          "(generated in %.1f s)" % (spec.name, spec.corpus_tokens, spec.batch, spec.prompt_len,
                                     spec.gen_len, w.steps, time.time() - t0))
+    if args.copy_probe_mib > 0:
+        import torch
+        n = args.copy_probe_mib * (1 << 20) // 4
+        src_t = torch.ones(n, dtype=torch.int32, device="cuda:0")
+        dst_t = torch.empty_like(src_t)
+        torch.cuda.synchronize()
+        dst_t.copy_(src_t)
+        torch.cuda.synchronize()
+        _log("copy probe: %d MiB read + %d MiB written by one copy kernel"
+             % (args.copy_probe_mib, args.copy_probe_mib))
+        del src_t, dst_t
     g = gpu_leg(w, args.steps, args.warmup)
 
     per_step_ms = g["event_ms"] / args.steps
@@ -234,7 +275,7 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": None,
+            "traffic": measured_traffic(spec.name),
             "algo_bytes_per_launch": algo_bytes_per_launch,
             "avg_launch_ms": per_step_ms,
         },

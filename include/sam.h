@@ -59,6 +59,8 @@ extern "C" {
 #define SAM_SOURCE_NONE     0   /* match_len == 0, no draft */
 #define SAM_SOURCE_DYNAMIC  1
 #define SAM_SOURCE_STATIC   2
+#define SAM_SOURCE_AUXILIARY 3  /* only with sam_batch_set_threshold: the match is not longer
+                                   than the auxiliary drafter's virtual length           */
 
 typedef struct sam_corpus sam_corpus;
 typedef struct sam_batch  sam_batch;
@@ -184,6 +186,16 @@ int sam_batch_step(sam_batch *batch, const int32_t *accepted, const int32_t *cou
 int sam_batch_reset(sam_batch *batch, const int32_t *slots, int32_t n_slots,
                     const int32_t *prompt_tokens, const int64_t *prompt_offsets,
                     void *hip_stream);
+
+/*
+ * Hook for an auxiliary drafter (Section 3.4): the auxiliary method has the fixed
+ * virtual match length l_threshold; from the next sam_batch_step on, a sequence
+ * whose chosen match length is <= l_threshold gets source = SAM_SOURCE_AUXILIARY
+ * (match_len, draft and draft_len are still those of the automaton, so the
+ * caller may use either).  l_threshold < 0 (the initial state) switches the hook
+ * off.  Host-side only; takes effect for launches enqueued after the call.
+ */
+int sam_batch_set_threshold(sam_batch *batch, int32_t l_threshold);
 
 /*
  * Both cursors of every sequence, for checking: static (s1, l1) and dynamic

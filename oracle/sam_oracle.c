@@ -32,7 +32,12 @@
  *   - a draft is cut at the end of the text and padded with -1;
  *   - a cursor at the root (l = 0) yields no draft;
  *   - ties between the two sources go to the dynamic one and there is no
- *     fallback to the other source when the chosen draft is empty.
+ *     fallback to the other source when the chosen draft is empty;
+ *   - the auxiliary drafter of Section 3.4 has the fixed virtual match length
+ *     l_threshold; by analogy with the strict "l1 > l2 + l_bias" rule the
+ *     automaton's draft is kept only if its match length is strictly above it,
+ *     otherwise the source is reported as "auxiliary" (3); l_threshold < 0
+ *     means there is no auxiliary drafter.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -383,9 +388,10 @@ int oseq_feed(oseq *q, const int32_t *tokens, int32_t count)
 }
 
 /* Select the source and read the draft.
- * out5 = { match_len, source (0 none, 1 dynamic, 2 static), draft_len,
+ * out5 = { match_len, source (0 none, 1 dynamic, 2 static, 3 auxiliary), draft_len,
  *          min_endpos of the chosen state (or -1), chosen state id (or -1) } */
-void oseq_draft(const oseq *q, int32_t L, int32_t l_bias, int32_t *out5, int32_t *draft)
+void oseq_draft(const oseq *q, int32_t L, int32_t l_bias, int32_t l_threshold, int32_t *out5,
+                int32_t *draft)
 {
     int32_t use_static = q->stat && (q->l1 > q->l2 + l_bias);
     int32_t ml = use_static ? q->l1 : q->l2;
@@ -406,6 +412,7 @@ void oseq_draft(const oseq *q, int32_t L, int32_t l_bias, int32_t *out5, int32_t
             dl++;
         }
     }
+    if (l_threshold >= 0 && ml <= l_threshold) src = 3;
     out5[0] = ml; out5[1] = src; out5[2] = dl; out5[3] = p; out5[4] = st;
 }
 
@@ -431,13 +438,13 @@ void oseq_counters(const oseq *q, int64_t *out8)
  * read the draft.  accepted is [B, A], counts [B]; outputs match_len/source/
  * draft_len [B] and draft [B, L].  A count of 0 leaves the sequence as it is. */
 int obatch_step(oseq **seqs, int32_t B, const int32_t *accepted, const int32_t *counts,
-                int32_t A, int32_t L, int32_t l_bias,
+                int32_t A, int32_t L, int32_t l_bias, int32_t l_threshold,
                 int32_t *match_len, int32_t *source, int32_t *draft_len, int32_t *draft)
 {
     for (int32_t b = 0; b < B; b++) {
         int32_t out5[5];
         if (oseq_feed(seqs[b], accepted + (size_t)b * A, counts[b]) != 0) return -1;
-        oseq_draft(seqs[b], L, l_bias, out5, draft + (size_t)b * L);
+        oseq_draft(seqs[b], L, l_bias, l_threshold, out5, draft + (size_t)b * L);
         match_len[b] = out5[0];
         source[b] = out5[1];
         draft_len[b] = out5[2];

@@ -72,7 +72,7 @@ def lib():
             L.oseq_free.argtypes = [C.c_void_p]
             L.oseq_feed.argtypes = [C.c_void_p, _i32p, C.c_int32]
             L.oseq_feed.restype = C.c_int
-            L.oseq_draft.argtypes = [C.c_void_p, C.c_int32, C.c_int32, _i32p, _i32p]
+            L.oseq_draft.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _i32p, _i32p]
             L.oseq_cursors.argtypes = [C.c_void_p, _i32p]
             L.oseq_dynamic.argtypes = [C.c_void_p]
             L.oseq_dynamic.restype = C.c_void_p
@@ -80,7 +80,7 @@ def lib():
             L.oseq_text_len.restype = C.c_int64
             L.oseq_counters.argtypes = [C.c_void_p, _i64p]
             L.obatch_step.argtypes = [C.POINTER(C.c_void_p), C.c_int32, _i32p, _i32p,
-                                      C.c_int32, C.c_int32, C.c_int32,
+                                      C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                       _i32p, _i32p, _i32p, _i32p]
             L.obatch_step.restype = C.c_int
             _lib = L
@@ -187,11 +187,11 @@ class Sequence:
         if self._L.oseq_feed(self._h, _p32(t), len(t)) != 0:
             raise MemoryError("oseq_feed failed")
 
-    def draft(self, L: int, l_bias: int = 0):
+    def draft(self, L: int, l_bias: int = 0, l_threshold: int = -1):
         """-> dict(match_len, source, draft_len, endpos, state, draft[L])."""
         o = np.zeros(5, dtype=np.int32)
         d = np.empty(L, dtype=np.int32)
-        self._L.oseq_draft(self._h, L, l_bias, _p32(o), _p32(d))
+        self._L.oseq_draft(self._h, L, l_bias, l_threshold, _p32(o), _p32(d))
         return dict(match_len=int(o[0]), source=int(o[1]), draft_len=int(o[2]),
                     endpos=int(o[3]), state=int(o[4]), draft=d)
 
@@ -221,12 +221,13 @@ class Batch:
     returns (match_len, source, draft_len, draft)."""
 
     def __init__(self, static: Sam | None, corpus, prompts, max_accept: int,
-                 draft_len: int, l_bias: int = 0):
+                 draft_len: int, l_bias: int = 0, l_threshold: int = -1):
         self._L = lib()
         self.seqs = [Sequence(static, corpus) for _ in range(len(prompts))]
         for s, p in zip(self.seqs, prompts):
             s.feed(p)
         self.A, self.Ld, self.l_bias = max_accept, draft_len, l_bias
+        self.l_threshold = l_threshold
         self._arr = (C.c_void_p * len(self.seqs))(*[s._h for s in self.seqs])
 
     def step(self, accepted, counts):
@@ -238,7 +239,8 @@ class Batch:
         dl = np.empty(B, dtype=np.int32)
         d = np.empty((B, self.Ld), dtype=np.int32)
         rc = self._L.obatch_step(self._arr, B, _p32(acc), _p32(cnt), self.A, self.Ld,
-                                 self.l_bias, _p32(ml), _p32(src), _p32(dl), _p32(d))
+                                 self.l_bias, self.l_threshold, _p32(ml), _p32(src), _p32(dl),
+                                 _p32(d))
         if rc != 0:
             raise MemoryError("obatch_step failed")
         return ml, src, dl, d

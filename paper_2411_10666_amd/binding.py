@@ -17,7 +17,7 @@ from . import build as _build
 
 SAM_OK, SAM_EINVAL, SAM_ENOMEM, SAM_ECAPACITY, SAM_ETOKEN, SAM_EDEVICE = 0, -1, -2, -3, -4, -5
 SAM_STATUS_CAPACITY, SAM_STATUS_TOKEN, SAM_STATUS_COUNT, SAM_STATUS_INTERNAL = 1, 2, 4, 8
-SAM_SOURCE_NONE, SAM_SOURCE_DYNAMIC, SAM_SOURCE_STATIC = 0, 1, 2
+SAM_SOURCE_NONE, SAM_SOURCE_DYNAMIC, SAM_SOURCE_STATIC, SAM_SOURCE_AUXILIARY = 0, 1, 2, 3
 
 EXPORTS = [
     "sam_last_error", "sam_build", "sam_build_host_only", "sam_corpus_info",
@@ -25,6 +25,7 @@ EXPORTS = [
     "sam_batch_step", "sam_batch_debug", "sam_batch_sizes", "sam_batch_status",
     "sam_batch_info", "sam_batch_free", "sam_set_layout_override",
     "sam_batch_reset", "sam_set_progress_callback",
+    "sam_batch_set_threshold",
 ]
 
 
@@ -55,6 +56,7 @@ def _load():
     L.sam_batch_init.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, C.POINTER(vp)]
     L.sam_batch_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     L.sam_set_progress_callback.argtypes = [PROGRESS_FN, vp]
+    L.sam_batch_set_threshold.argtypes = [vp, i32]
     L.sam_batch_reset.argtypes = [vp, vp, i32, vp, vp, vp]
     L.sam_batch_debug.argtypes = [vp, vp, vp, vp, vp, vp]
     L.sam_batch_sizes.argtypes = [vp, vp, vp, vp, vp]
@@ -206,6 +208,10 @@ def sam_batch_reset(batch: Batch, slots, prompt_tokens, prompt_offsets, stream=N
                                 _dev_ptr(prompt_tokens, torch.int32, "prompt_tokens"),
                                 _dev_ptr(prompt_offsets, torch.int64, "prompt_offsets"),
                                 _stream_ptr(stream)))
+
+
+def sam_batch_set_threshold(batch: Batch, l_threshold: int) -> None:
+    _check(_lib.sam_batch_set_threshold(batch._h, l_threshold))
 
 
 class StepPlan:

@@ -256,6 +256,7 @@ int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
     v.max_accept = max_accept;
     v.draft_len = draft_len;
     v.l_bias = l_bias;
+    v.l_threshold = -1;
     v.has_static = corpus ? 1 : 0;
     const size_t b_text = (size_t)batch * max_seq_len * sizeof(int32_t);
     const size_t b_rec = (size_t)batch * v.max_states * rec_bytes;
@@ -384,6 +385,13 @@ int sam_batch_status(const sam_batch *bt, uint32_t *status, void *hip_stream)
     HIP_TRY(hipMemcpyAsync(status, bt->view.status, sizeof(uint32_t), hipMemcpyDeviceToHost,
                            stream));
     HIP_TRY(hipStreamSynchronize(stream));
+    return SAM_OK;
+}
+
+int sam_batch_set_threshold(sam_batch *bt, int32_t l_threshold)
+{
+    if (!bt) return fail(SAM_EINVAL, "sam_batch_set_threshold: batch is NULL");
+    bt->view.l_threshold = l_threshold < 0 ? -1 : l_threshold;
     return SAM_OK;
 }
 

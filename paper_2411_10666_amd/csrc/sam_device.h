@@ -34,6 +34,7 @@ struct BatchView {
     int32_t   max_accept;
     int32_t   draft_len;
     int32_t   l_bias;
+    int32_t   l_threshold;     // < 0: no auxiliary drafter
     int32_t   has_static;
     int32_t  *dyn_text;        // [batch, max_seq_len]
     void     *dyn_rec;         // [batch, max_states] records of the chosen layout

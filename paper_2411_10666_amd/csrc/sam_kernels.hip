@@ -638,7 +638,9 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
     if (lane == 0) {
         match_len[b] = (int32_t)ml;
         draft_len[b] = dl;
-        source[b] = ml == 0 ? 0 : (use_static ? 2 : 1);
+        int src = ml == 0 ? 0 : (use_static ? 2 : 1);
+        if (B.l_threshold >= 0 && (int64_t)ml <= (int64_t)B.l_threshold) src = 3;
+        source[b] = src;
     }
 }
 

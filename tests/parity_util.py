@@ -6,7 +6,7 @@ import numpy as np
 
 
 def run_gpu(corpus, vocab, prompts, accepted, counts, max_seq_len, max_accept, draft_len,
-            l_bias=0, gpu_corpus=None, collect_every=1):
+            l_bias=0, gpu_corpus=None, collect_every=1, l_threshold=-1):
     """prompts: list of int32 arrays.  accepted [S,B,A], counts [S,B].
     -> list over steps of dict(match_len, source, draft_len, draft, cursors[B,4], sizes[B,3])."""
     import torch
@@ -22,6 +22,8 @@ def run_gpu(corpus, vocab, prompts, accepted, counts, max_seq_len, max_accept, d
     d_off = torch.from_numpy(offs).to(dev)
     batch = sam.sam_batch_init(gpu_corpus, d_tok, d_off, B, vocab, max_seq_len, max_accept,
                                draft_len, l_bias)
+    if l_threshold >= 0:
+        sam.sam_batch_set_threshold(batch, l_threshold)
     d_acc = torch.from_numpy(np.ascontiguousarray(accepted, dtype=np.int32)).to(dev)
     d_cnt = torch.from_numpy(np.ascontiguousarray(counts, dtype=np.int32)).to(dev)
     i32 = dict(dtype=torch.int32, device=dev)
@@ -46,11 +48,11 @@ def run_gpu(corpus, vocab, prompts, accepted, counts, max_seq_len, max_accept, d
 
 
 def run_oracle(corpus, prompts, accepted, counts, max_accept, draft_len, l_bias=0,
-               static=None, collect_every=1):
+               static=None, collect_every=1, l_threshold=-1):
     from oracle.sam_oracle import Batch, Sam
     if static is None and corpus is not None:
         static = Sam.build(corpus)
-    ob = Batch(static, corpus, prompts, max_accept, draft_len, l_bias)
+    ob = Batch(static, corpus, prompts, max_accept, draft_len, l_bias, l_threshold)
     out = []
     S = len(counts)
     for s in range(S):

@@ -254,6 +254,22 @@ def test_unseen_token_resets_to_root_and_empty_cases():
     assert Sam.build([]).num_states == 1
 
 
+def test_auxiliary_threshold_rule():
+    """Section 3.4: the auxiliary drafter has virtual length l_threshold; the
+    automaton's draft is kept only for strictly longer matches."""
+    corpus = np.array([1, 2, 3, 4, 5, 1, 2, 9], dtype=np.int32)
+    st = Sam.build(corpus)
+    seq = Sequence(st, corpus)
+    seq.feed([7, 1, 2, 3])                       # static match "1 2 3", length 3
+    for thr, want in [(-1, 2), (0, 2), (2, 2), (3, 3), (4, 3)]:
+        d = seq.draft(4, 0, thr)
+        assert d["match_len"] == 3 and d["source"] == want
+        assert d["draft"].tolist() == [4, 5, 1, 2]
+    seq.feed([8])                                # no match at all
+    assert seq.draft(4, 0, -1)["source"] == 0
+    assert seq.draft(4, 0, 0)["source"] == 3
+
+
 def test_batch_matches_single_sequences():
     rng = np.random.default_rng(9)
     corpus = np.array(_rand_text(rng, 300, 6), dtype=np.int32)

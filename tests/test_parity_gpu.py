@@ -201,6 +201,20 @@ def test_device_side_faults_leave_other_sequences_intact():
     assert_same(g, r)
 
 
+@pytest.mark.parametrize("l_threshold,l_bias", [(0, 0), (2, 2), (5, 5)])
+def test_auxiliary_threshold_hook(l_threshold, l_bias):
+    B, T, A, L, steps, vocab = 9, 300, 6, 8, 40, 3
+    _say("auxiliary threshold %d" % l_threshold)
+    corpus, prompts, acc, counts = _random_case(50 + l_threshold, vocab, 2000, B, T, A, L, steps)
+    g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L, l_bias=l_bias,
+                           l_threshold=l_threshold)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L, l_bias=l_bias, l_threshold=l_threshold)
+    assert status == 0
+    assert_same(g, r)
+    srcs = np.concatenate([x["source"] for x in r])
+    assert (srcs == 3).any() and (srcs != 3).any()
+
+
 def test_reset_recycles_sequences():
     """Continuous batching: some sequences are replaced by new requests in the
     middle of a run; the others carry on untouched."""
