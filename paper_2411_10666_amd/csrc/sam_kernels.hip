@@ -42,6 +42,14 @@ __device__ __forceinline__ void pin_s(uint32_t &v)
     asm volatile("" : "+s"(v));
 }
 
+// Same for a per-lane value.  Used on the step's token vector: once the load has
+// landed before the token loop, reading a lane of it inside the loop no longer
+// makes the wave wait for the stores of the previous token.
+__device__ __forceinline__ void pin_v(uint32_t &v)
+{
+    asm volatile("" : "+v"(v));
+}
+
 __device__ __forceinline__ void order_memory()
 {
     // stores and later loads of one wavefront reach memory in program order;
@@ -547,7 +555,8 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
             bool stop = false;
             for (int64_t base = 0; base < count && !stop; base += 64) {
                 const int m = (int)((count - base) < 64 ? (count - base) : 64);
-                const uint32_t tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
+                uint32_t tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
+                pin_v(tv);
                 for (int i = 0; i < m; i++) {
                     const uint32_t t = lane_get(tv, i);
                     if (t >= vocab) { stop = true; break; }
@@ -576,7 +585,8 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
         bool stop = false;
         for (int64_t base = 0; base < count && !stop; base += 64) {
             const int m = (int)((count - base) < 64 ? (count - base) : 64);
-            const uint32_t tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
+            uint32_t tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
+            pin_v(tv);
             c.pf_ok = false;
             const uint32_t n_chunk = c.n;
             int fed = 0;
