@@ -39,6 +39,10 @@ class SamError(RuntimeError):
 
 
 def _load():
+    # PyTorch ships its own copy of the HIP runtime.  It has to be in the process
+    # before this library is, so that both resolve to one runtime (two copies in
+    # one process do not both find the GPU).
+    import torch  # noqa: F401
     path = _build.LIB
     if not os.path.exists(path):
         # nothing built yet: build once; a stale library is the caller's business

@@ -215,7 +215,15 @@ int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
         return fail(SAM_EINVAL, "sam_batch_init: draft_len must be in 1 .. 1024");
     if (corpus && !corpus->on_device)
         return fail(SAM_EINVAL, "sam_batch_init: corpus was built host-only");
-    if (corpus) vocab = corpus->host.vocab;
+    if (corpus) {
+        int dev = -1;
+        HIP_TRY(hipGetDevice(&dev));
+        if (dev != corpus->device)
+            return fail(SAM_EINVAL, "sam_batch_init: the corpus lives on device " +
+                                        std::to_string(corpus->device) + ", the current device is " +
+                                        std::to_string(dev));
+        vocab = corpus->host.vocab;
+    }
     if (vocab < 1) return fail(SAM_EINVAL, "sam_batch_init: vocab must be >= 1");
     hipStream_t stream = (hipStream_t)hip_stream;
 
