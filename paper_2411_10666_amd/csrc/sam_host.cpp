@@ -8,6 +8,7 @@
 
 #include <stdlib.h>
 #include <string.h>
+#include <sys/mman.h>
 
 #include <new>
 
@@ -16,6 +17,35 @@
 namespace sam {
 
 HostSam::~HostSam() { free(slots); }
+
+namespace {
+constexpr size_t kHuge = 2u << 20;
+void *huge_alloc(size_t bytes)
+{
+    const size_t rounded = (bytes + kHuge - 1) / kHuge * kHuge;
+    void *p = aligned_alloc(kHuge, rounded);
+    if (p) (void)madvise(p, rounded, MADV_HUGEPAGE);
+    return p;
+}
+}  // namespace
+
+template <class T>
+bool HugeArray<T>::reserve(size_t cap)
+{
+    release();
+    p_ = (T *)huge_alloc(cap * sizeof(T));
+    return p_ != nullptr;
+}
+
+template <class T>
+void HugeArray<T>::release()
+{
+    free(p_);
+    p_ = nullptr;
+    n_ = 0;
+}
+
+template class HugeArray<uint32_t>;
 
 namespace {
 
@@ -65,17 +95,18 @@ int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string
     }
     try {
         text.assign(tokens, tokens + n);
-        const size_t cap = (size_t)2 * n + 2;
-        len.reserve(cap);
-        link.reserve(cap);
-        endpos.reserve(cap);
-        head.reserve(cap);
         root.assign((size_t)vocab, RootEnt{0, 0});
     } catch (const std::bad_alloc &) {
+        err = "sam_build: out of host memory for the corpus text";
+        return SAM_ENOMEM;
+    }
+    const size_t cap = (size_t)2 * n + 2;     // states <= 2n - 1 (n >= 2), 2 for n = 1
+    if (!len.reserve(cap) || !link.reserve(cap) || !endpos.reserve(cap) || !head.reserve(cap)) {
         err = "sam_build: out of host memory for the state arrays";
         return SAM_ENOMEM;
     }
-    slots = (Slot *)aligned_alloc(128, n_slots * sizeof(Slot));
+    // the table is probed at random: 2 MB pages keep the host TLB out of the way
+    slots = (Slot *)huge_alloc(n_slots * sizeof(Slot));
     if (!slots) {
         err = "sam_build: out of host memory for the transition table";
         return SAM_ENOMEM;
@@ -159,7 +190,7 @@ int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string
     }
     for (int32_t t = 0; t < vocab; t++)
         if (root[t].dst) root[t].endpos = endpos[root[t].dst];
-    std::vector<uint32_t>().swap(head);
+    head.release();
     return SAM_OK;
 }
 
@@ -178,6 +209,6 @@ void HostSam::make_linkrec(std::vector<LinkRec> &out) const
     for (uint32_t s = 1; s < n_states; s++) out[s] = LinkRec{link[s], len[link[s]]};
 }
 
-void HostSam::release_build_only() { std::vector<uint32_t>().swap(head); }
+void HostSam::release_build_only() { head.release(); }
 
 }  // namespace sam

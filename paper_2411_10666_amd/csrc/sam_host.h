@@ -9,6 +9,28 @@
 
 namespace sam {
 
+// Fixed-capacity array on 2 MB pages (the state arrays are read at random while
+// building; small pages would make the host TLB the bottleneck).
+template <class T>
+class HugeArray {
+public:
+    HugeArray() = default;
+    HugeArray(const HugeArray &) = delete;
+    HugeArray &operator=(const HugeArray &) = delete;
+    ~HugeArray() { release(); }
+    bool reserve(size_t cap);            // false: out of memory
+    void release();
+    void push_back(const T &v) { p_[n_++] = v; }
+    T &operator[](size_t i) { return p_[i]; }
+    const T &operator[](size_t i) const { return p_[i]; }
+    size_t size() const { return n_; }
+    const T *data() const { return p_; }
+
+private:
+    T *p_ = nullptr;
+    size_t n_ = 0;
+};
+
 struct HostSam {
     int64_t  n_tokens = 0;
     int32_t  vocab = 0;
@@ -17,8 +39,8 @@ struct HostSam {
     uint64_t n_buckets = 0;
 
     std::vector<int32_t>  text;
-    std::vector<uint32_t> len, link, endpos;
-    std::vector<uint32_t> head;  // newest slot of each state's transition list (build only)
+    HugeArray<uint32_t>   len, link, endpos;
+    HugeArray<uint32_t>   head;  // newest slot of each state's transition list (build only)
     std::vector<RootEnt>  root;  // direct-indexed transitions of the root
     Slot *slots = nullptr;       // n_buckets * 8, 128-byte aligned
 
