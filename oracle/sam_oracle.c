@@ -33,6 +33,14 @@
  *   - a cursor at the root (l = 0) yields no draft;
  *   - ties between the two sources go to the dynamic one and there is no
  *     fallback to the other source when the chosen draft is empty;
+ *   - tree drafts (Appendix A.1 freq, Algorithm 3, Algorithm 4): the root's freq
+ *     starts at 0 (it is made neither by expansion nor by cloning); Algorithm
+ *     3's dfs visits every state once (as printed it would re-add a shared
+ *     child's count on every visit); TopK ranks successors by freq, ties by
+ *     smaller token id; probabilities are the double quotient rounded to
+ *     float; Prim multiplies in float, pops the largest probability, ties to
+ *     the entry pushed first; the start token is element 0 of the draft (its
+ *     parent is -1) and counts towards MAX_SIZE;
  *   - the auxiliary drafter of Section 3.4 has the fixed virtual match length
  *     l_threshold; by analogy with the strict "l1 > l2 + l_bias" rule the
  *     automaton's draft is kept only if its match length is strictly above it,
@@ -70,6 +78,14 @@ typedef struct {
     int64_t  c_clone;       /* clones made                                      */
     int64_t  c_copy;        /* transitions copied into clones                   */
     int64_t  c_expand_probe;/* "t in p.next" tests made by Expand               */
+    /* tree drafts: filled by osam_init_topk */
+    uint8_t  *is_clone;     /* per state, set by Expand (freq starts at 0)      */
+    int64_t   cap_clone;
+    uint64_t *freq;         /* per state                                        */
+    int32_t   topk;         /* k, 0 = not computed                              */
+    int32_t  *topk_tok;     /* [n_states * k], -1 = unused entry                */
+    int32_t  *topk_dst;
+    float    *topk_prob;
 } osam;
 
 /* counters of a cursor walking an automaton with Transfer */
@@ -156,6 +172,11 @@ void osam_free(osam *S)
     if (!S) return;
     for (int64_t i = 0; i < S->n_states; i++) free(S->st[i].next);
     free(S->st);
+    free(S->is_clone);
+    free(S->freq);
+    free(S->topk_tok);
+    free(S->topk_dst);
+    free(S->topk_prob);
     free(S);
 }
 
@@ -185,6 +206,16 @@ int osam_expand(osam *S, int32_t t)
         } else {
             int32_t cl = expand_state(S, -1, -1, -1);
             if (cl < 0) return -1;
+            if (cl >= S->cap_clone) {
+                int64_t nc = S->cap_clone ? S->cap_clone * 2 : 64;
+                while (nc <= cl) nc *= 2;
+                uint8_t *nb = (uint8_t *)realloc(S->is_clone, (size_t)nc);
+                if (!nb) return -1;
+                memset(nb + S->cap_clone, 0, (size_t)(nc - S->cap_clone));
+                S->is_clone = nb;
+                S->cap_clone = nc;
+            }
+            S->is_clone[cl] = 1;
             ostate *Q = &S->st[q];
             ostate *C = &S->st[cl];
             C->link = Q->link;
@@ -257,6 +288,124 @@ void osam_transfer(const osam *S, int32_t t, int32_t *s_io, int32_t *l_io, owalk
     }
     *s_io = s;
     *l_io = l;
+}
+
+/* ---- top-k successors and transition probabilities (Algorithm 3) -------- */
+
+static int is_clone_state(const osam *S, int64_t v)
+{
+    return v < S->cap_clone && S->is_clone[v];
+}
+
+/* dfs of Algorithm 3 with an explicit stack (the automaton of a long text is
+ * deeper than any call stack): a state's successors are finished first, then
+ * its freq is its own start value plus theirs, then its TopK is taken. */
+int osam_init_topk(osam *S, int32_t k)
+{
+    const int64_t n = S->n_states;
+    if (k < 1) return -1;
+    free(S->freq); free(S->topk_tok); free(S->topk_dst); free(S->topk_prob);
+    S->freq = (uint64_t *)calloc((size_t)n, sizeof(uint64_t));
+    S->topk_tok = (int32_t *)malloc((size_t)n * k * sizeof(int32_t));
+    S->topk_dst = (int32_t *)malloc((size_t)n * k * sizeof(int32_t));
+    S->topk_prob = (float *)malloc((size_t)n * k * sizeof(float));
+    uint8_t *done = (uint8_t *)calloc((size_t)n, 1);
+    int32_t *stack = (int32_t *)malloc((size_t)n * sizeof(int32_t));
+    int32_t *child = (int32_t *)calloc((size_t)n, sizeof(int32_t));   /* next successor to visit */
+    if (!S->freq || !S->topk_tok || !S->topk_dst || !S->topk_prob || !done || !stack || !child) {
+        free(done); free(stack); free(child);
+        return -1;
+    }
+    S->topk = k;
+    for (int64_t v = 0; v < n; v++)
+        S->freq[v] = (v == 0 || is_clone_state(S, v)) ? 0 : 1;
+    int64_t sp = 0;
+    stack[sp++] = 0;                       /* Init_topk: dfs(root) */
+    done[0] = 2;                           /* 2 = on the stack, 1 = finished */
+    while (sp > 0) {
+        int32_t v = stack[sp - 1];
+        ostate *st = &S->st[v];
+        if (child[v] < st->n_next) {
+            int32_t u = st->next[child[v]++].dst;
+            if (!done[u]) { done[u] = 2; stack[sp++] = u; }
+            continue;
+        }
+        /* all successors finished */
+        for (int32_t j = 0; j < st->n_next; j++) S->freq[v] += S->freq[st->next[j].dst];
+        for (int32_t i = 0; i < k; i++) {
+            /* i-th largest successor by (freq desc, token asc) not taken yet */
+            int32_t best = -1;
+            for (int32_t j = 0; j < st->n_next; j++) {
+                int taken = 0;
+                for (int32_t h = 0; h < i; h++)
+                    if (S->topk_tok[(size_t)v * k + h] == st->next[j].token) taken = 1;
+                if (taken) continue;
+                if (best < 0 || S->freq[st->next[j].dst] > S->freq[st->next[best].dst]) best = j;
+            }
+            if (best < 0) {
+                S->topk_tok[(size_t)v * k + i] = -1;
+                S->topk_dst[(size_t)v * k + i] = -1;
+                S->topk_prob[(size_t)v * k + i] = 0.0f;
+            } else {
+                S->topk_tok[(size_t)v * k + i] = st->next[best].token;
+                S->topk_dst[(size_t)v * k + i] = st->next[best].dst;
+                S->topk_prob[(size_t)v * k + i] =
+                    (float)((double)S->freq[st->next[best].dst] / (double)S->freq[v]);
+            }
+        }
+        done[v] = 1;
+        sp--;
+    }
+    free(done); free(stack); free(child);
+    return 0;
+}
+
+void osam_dump_topk(const osam *S, uint64_t *freq, int32_t *tok, int32_t *dst, float *prob)
+{
+    memcpy(freq, S->freq, (size_t)S->n_states * sizeof(uint64_t));
+    memcpy(tok, S->topk_tok, (size_t)S->n_states * S->topk * sizeof(int32_t));
+    memcpy(dst, S->topk_dst, (size_t)S->n_states * S->topk * sizeof(int32_t));
+    memcpy(prob, S->topk_prob, (size_t)S->n_states * S->topk * sizeof(float));
+}
+
+/* ---- Prim (Algorithm 4): best-first tree draft --------------------------- */
+
+/* Returns the number of draft entries written (<= max_size).  Entry 0 is the
+ * start token with parent -1 and probability 1. */
+int32_t osam_prim(const osam *S, int32_t s, int32_t t, int32_t max_size,
+                  int32_t *tokens, int32_t *parents, float *probs)
+{
+    const int32_t k = S->topk;
+    if (k < 1 || max_size < 1) return 0;
+    const int64_t cap = (int64_t)max_size * k + 1;
+    float   *qp = (float *)malloc((size_t)cap * sizeof(float));
+    int32_t *qs = (int32_t *)malloc((size_t)cap * sizeof(int32_t));
+    int32_t *qt = (int32_t *)malloc((size_t)cap * sizeof(int32_t));
+    int32_t *qpar = (int32_t *)malloc((size_t)cap * sizeof(int32_t));
+    uint8_t *qlive = (uint8_t *)calloc((size_t)cap, 1);
+    if (!qp || !qs || !qt || !qpar || !qlive) { free(qp); free(qs); free(qt); free(qpar); free(qlive); return -1; }
+    int64_t qn = 0;
+    qp[qn] = 1.0f; qs[qn] = s; qt[qn] = t; qpar[qn] = -1; qlive[qn] = 1; qn++;
+    int32_t dn = 0;
+    while (dn < max_size) {
+        /* q.top(): largest probability, the entry pushed first among equals */
+        int64_t best = -1;
+        for (int64_t i = 0; i < qn; i++)
+            if (qlive[i] && (best < 0 || qp[i] > qp[best])) best = i;
+        if (best < 0) break;
+        qlive[best] = 0;                                   /* q.pop() */
+        tokens[dn] = qt[best]; parents[dn] = qpar[best]; probs[dn] = qp[best];
+        const int32_t me = dn++;
+        const int32_t st = qs[best];
+        for (int32_t i = 0; i < k; i++) {
+            if (S->topk_dst[(size_t)st * k + i] < 0) continue;
+            float pn = qp[best] * S->topk_prob[(size_t)st * k + i];
+            qp[qn] = pn; qs[qn] = S->topk_dst[(size_t)st * k + i];
+            qt[qn] = S->topk_tok[(size_t)st * k + i]; qpar[qn] = me; qlive[qn] = 1; qn++;
+        }
+    }
+    free(qp); free(qs); free(qt); free(qpar); free(qlive);
+    return dn;
 }
 
 /* ---- accessors --------------------------------------------------------- */

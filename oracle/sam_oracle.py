@@ -67,6 +67,12 @@ def lib():
             L.osam_dump_trans.argtypes = [C.c_void_p, _i32p, _i32p, _i32p]
             L.osam_dump_trans.restype = C.c_int64
             L.osam_counters.argtypes = [C.c_void_p, _i64p]
+            L.osam_init_topk.argtypes = [C.c_void_p, C.c_int32]
+            L.osam_init_topk.restype = C.c_int
+            L.osam_dump_topk.argtypes = [C.c_void_p, C.c_void_p, _i32p, _i32p, C.c_void_p]
+            L.osam_prim.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, _i32p, _i32p,
+                                    C.c_void_p]
+            L.osam_prim.restype = C.c_int32
             L.oseq_new.argtypes = [C.c_void_p, _i32p, C.c_int64]
             L.oseq_new.restype = C.c_void_p
             L.oseq_free.argtypes = [C.c_void_p]
@@ -161,6 +167,35 @@ class Sam:
         o = np.zeros(5, dtype=np.int64)
         self._L.osam_counters(self._h, _p64(o))
         return dict(zip(["insert", "redirect", "clone", "copy", "expand_probe"], o.tolist()))
+
+    def init_topk(self, k: int) -> None:
+        """Algorithm 3: freq per state, top-k successors and their probabilities."""
+        if self._L.osam_init_topk(self._h, k) != 0:
+            raise MemoryError("osam_init_topk failed")
+        self._k = k
+
+    def topk(self):
+        """(freq uint64 [n], token int32 [n,k], target int32 [n,k], prob float32 [n,k]);
+        unused entries have token = target = -1."""
+        n, k = self.num_states, self._k
+        freq = np.empty(n, dtype=np.uint64)
+        tok = np.empty((n, k), dtype=np.int32)
+        dst = np.empty((n, k), dtype=np.int32)
+        prob = np.empty((n, k), dtype=np.float32)
+        self._L.osam_dump_topk(self._h, freq.ctypes.data_as(C.c_void_p), _p32(tok), _p32(dst),
+                               prob.ctypes.data_as(C.c_void_p))
+        return freq, tok, dst, prob
+
+    def prim(self, state: int, token: int, max_size: int):
+        """Algorithm 4 -> (tokens, parents, probs), each of the draft's length."""
+        t = np.empty(max_size, dtype=np.int32)
+        p = np.empty(max_size, dtype=np.int32)
+        pr = np.empty(max_size, dtype=np.float32)
+        n = self._L.osam_prim(self._h, state, token, max_size, _p32(t), _p32(p),
+                              pr.ctypes.data_as(C.c_void_p))
+        if n < 0:
+            raise MemoryError("osam_prim failed")
+        return t[:n], p[:n], pr[:n]
 
 
 class Sequence:

@@ -289,3 +289,118 @@ def test_batch_matches_single_sequences():
             r = singles[b].draft(L, 0)
             assert (ml[b], src[b], dl[b]) == (r["match_len"], r["source"], r["draft_len"])
             assert (d[b] == r["draft"]).all()
+
+
+# --------------------------------------------------------------------------
+# tree drafts: Algorithm 3 (freq, top-k, probabilities) and Algorithm 4 (Prim)
+
+def _freq_closed_form(text):
+    """freq(v) counted from the definition: a path from v that ends in the state
+    of the whole prefix T[0..j) contributes 1.  Such a path spells T[e..j) for an
+    end position e of v, and it lands in that state iff the string it completes,
+    of length j - e + len(v), is longer than the longest suffix of T[0..j) that
+    ends at more places than that prefix does (those suffixes are other states)."""
+    n = len(text)
+    occ = substrings(text)
+    other = [0] * (n + 1)        # other[j]: longest suffix of T[:j] with more end positions
+    for j in range(1, n + 1):
+        for L in range(j - 1, 0, -1):
+            if len(occ[tuple(text[j - L:j])]) > len(occ[tuple(text[:j])]):
+                other[j] = L
+                break
+    info = endpos_classes(text)
+    out = {}
+    for key, d in info.items():
+        length = key[0]
+        ends = occ[d["longest"]] if length else list(range(0, n + 1))
+        f = 0
+        for e in ends:
+            for j in range(max(e, 1), n + 1):
+                if j - e + length > other[j]:
+                    f += 1
+        out[key] = f
+    return out
+
+
+@pytest.mark.parametrize("seed,vocab,n", _cases()[:32])
+def test_freq_and_topk_against_definition(seed, vocab, n):
+    rng = np.random.default_rng(400 + seed)
+    text = _rand_text(rng, min(n, 40), vocab)
+    sam = Sam.build(text)
+    k = 1 + seed % 3
+    sam.init_topk(k)
+    freq, tok, dst, prob = sam.topk()
+    link, length, endpos, nxt = _structure(sam)
+    want = _freq_closed_form(text)
+    for v in range(sam.num_states):
+        assert int(freq[v]) == want[(length[v], endpos[v])], (v, text)
+        # top-k: successors ranked by (freq desc, token asc)
+        ranked = sorted(nxt[v].items(), key=lambda kv: (-int(freq[kv[1]]), kv[0]))[:k]
+        for i in range(k):
+            if i < len(ranked):
+                assert (tok[v, i], dst[v, i]) == ranked[i]
+                assert prob[v, i] == np.float32(float(freq[ranked[i][1]]) / float(freq[v]))
+            else:
+                assert tok[v, i] == -1 and dst[v, i] == -1
+        if v:
+            assert freq[v] >= 1
+        # successors partition what is left after the state's own start value
+        own = 0 if (v == 0 or length[v] != endpos[v]) else 1
+        assert int(freq[v]) == own + sum(int(freq[u]) for u in nxt[v].values())
+
+
+def test_freq_worked_example_abcbc():
+    """"ABCBC": freq by hand.  Prefix states 1,2,3,4,6 start at 1, clones 5,7 at 0.
+    6:{} -> 1; 4:{C:6} -> 2; 7:{B:4} -> 2; 3:{B:4} -> 3; 5:{C:7} -> 2;
+    2:{C:3} -> 4; 1:{B:2} -> 5; root:{A:1,B:5,C:7} -> 9."""
+    sam = Sam.build([0, 1, 2, 1, 2])
+    sam.init_topk(2)
+    freq, tok, dst, prob = sam.topk()
+    assert freq.tolist() == [9, 5, 4, 3, 2, 2, 1, 2]
+    assert tok[0].tolist() == [0, 1] and dst[0].tolist() == [1, 5]      # A (5), then B before C (2 = 2)
+    assert prob[0].tolist() == [np.float32(5 / 9), np.float32(2 / 9)]
+    t, p, pr = sam.prim(0, 7, 5)
+    # start token 7; then A (5/9), AB (5/9 * 4/5), ABC (* 3/4), then B (2/9) vs ABCB (1/3*2/3=2/9):
+    assert t.tolist()[:4] == [7, 0, 1, 2] and p.tolist()[:4] == [-1, 0, 1, 2]
+    assert pr[0] == np.float32(1.0) and pr[1] == np.float32(5 / 9)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_prim_is_best_first_over_the_topk_tree(seed):
+    rng = np.random.default_rng(500 + seed)
+    vocab = [2, 3, 6][seed % 3]
+    text = _rand_text(rng, int(rng.integers(5, 60)), vocab)
+    sam = Sam.build(text)
+    k = 1 + seed % 3
+    sam.init_topk(k)
+    freq, tok, dst, prob = sam.topk()
+    max_size = int(rng.integers(1, 24))
+    start_state = int(rng.integers(0, sam.num_states))
+    t, par, pr = sam.prim(start_state, 99, max_size)
+    assert t[0] == 99 and par[0] == -1 and pr[0] == np.float32(1.0)
+    # every entry is a top-k successor of its parent's state, with the product probability
+    state = [start_state]
+    for i in range(1, len(t)):
+        ps = state[par[i]]
+        j = tok[ps].tolist().index(t[i])
+        state.append(int(dst[ps, j]))
+        assert pr[i] == np.float32(pr[par[i]]) * prob[ps, j]
+        assert par[i] < i
+    assert all(pr[i] >= pr[i + 1] for i in range(len(pr) - 1))
+    # nothing outside the draft beats anything inside it: enumerate the whole
+    # top-k tree to the depth the draft can reach and compare the probability multisets
+    best = []
+    frontier = [(np.float32(1.0), start_state)]
+    for depth in range(max_size):
+        nxt_frontier = []
+        for p0, s0 in frontier:
+            best.append(float(p0))
+            for j in range(k):
+                if dst[s0, j] >= 0:
+                    nxt_frontier.append((np.float32(p0) * prob[s0, j], int(dst[s0, j])))
+        frontier = nxt_frontier
+        if len(best) > 4000:
+            break
+    best.sort(reverse=True)
+    assert sorted((float(x) for x in pr), reverse=True) == best[:len(pr)]
+    assert len(t) == min(max_size, len(best)) or len(best) > 4000
