@@ -117,6 +117,26 @@ int sam_corpus_export(const sam_corpus *corpus, int32_t *length, int32_t *link,
 int sam_corpus_find(const sam_corpus *corpus, int64_t state, int32_t token,
                     int64_t *target);
 
+/*
+ * Algorithm 3 (Appendix A.1): the frequency of every state (1 for states made by
+ * expansion, 0 for clones and the root, plus the frequencies of all successors),
+ * the k most frequent successors of every state (ties: smaller token id) and
+ * their probabilities freq(successor) / freq(state), rounded to float.  Computed
+ * on the host; if the corpus is on a device the table {token, target,
+ * probability} x k per state is copied there (12*k bytes per state).  k: 1 .. 8.
+ * May be called again with another k; synchronises the device.
+ * Errors: SAM_EINVAL, SAM_ENOMEM, SAM_EDEVICE.
+ */
+int sam_corpus_build_topk(sam_corpus *corpus, int32_t k);
+
+/*
+ * Copy the host-side result of sam_corpus_build_topk out: freq host uint64
+ * [n_states]; token, target host int32 [n_states, k] (-1 = unused entry); prob
+ * host float [n_states, k].  Any may be NULL.
+ */
+int sam_corpus_export_topk(const sam_corpus *corpus, uint64_t *freq, int32_t *token,
+                           int32_t *target, float *prob);
+
 void sam_corpus_free(sam_corpus *corpus);
 
 /*
@@ -168,6 +188,24 @@ int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
 int sam_batch_step(sam_batch *batch, const int32_t *accepted, const int32_t *counts,
                    int32_t *match_len, int32_t *draft, int32_t *draft_len,
                    int32_t *source, void *hip_stream);
+
+/*
+ * Tree draft from the static automaton (Section 3.2, Algorithm 4): for every
+ * sequence, best-first expansion over the top-k successors starting at the static
+ * cursor's state.  Entry 0 of a draft is the sequence's last token (parent -1,
+ * probability 1); every further entry is a token, the index of its parent entry
+ * and the product of the transition probabilities on its path (float, one
+ * rounding per edge).  The largest probability is expanded first, ties go to the
+ * entry created first.  A sequence with no tokens yet gets size 0.
+ *   max_size : entries per draft including entry 0, 1 .. 128.
+ *   tokens, parents : device, int32 [batch, max_size], padded with -1.
+ *   probs    : device, float [batch, max_size], padded with 0.
+ *   sizes    : device, int32 [batch].
+ * Needs a corpus with a top-k table.  Asynchronous; does not change the batch.
+ * Errors: SAM_EINVAL, SAM_EDEVICE.
+ */
+int sam_batch_tree_draft(sam_batch *batch, int32_t max_size, int32_t *tokens, int32_t *parents,
+                         float *probs, int32_t *sizes, void *hip_stream);
 
 /*
  * Recycle sequences of a live batch for new requests (continuous batching): each

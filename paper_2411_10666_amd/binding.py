@@ -25,7 +25,8 @@ EXPORTS = [
     "sam_batch_step", "sam_batch_debug", "sam_batch_sizes", "sam_batch_status",
     "sam_batch_info", "sam_batch_free", "sam_set_layout_override",
     "sam_batch_reset", "sam_set_progress_callback",
-    "sam_batch_set_threshold",
+    "sam_batch_set_threshold", "sam_corpus_build_topk", "sam_corpus_export_topk",
+    "sam_batch_tree_draft",
 ]
 
 
@@ -61,6 +62,9 @@ def _load():
     L.sam_batch_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     L.sam_set_progress_callback.argtypes = [PROGRESS_FN, vp]
     L.sam_batch_set_threshold.argtypes = [vp, i32]
+    L.sam_corpus_build_topk.argtypes = [vp, i32]
+    L.sam_corpus_export_topk.argtypes = [vp, vp, vp, vp, vp]
+    L.sam_batch_tree_draft.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     L.sam_batch_reset.argtypes = [vp, vp, i32, vp, vp, vp]
     L.sam_batch_debug.argtypes = [vp, vp, vp, vp, vp, vp]
     L.sam_batch_sizes.argtypes = [vp, vp, vp, vp, vp]
@@ -170,6 +174,37 @@ def sam_corpus_find(corpus: Corpus, state: int, token: int) -> int:
     t = C.c_int64()
     _check(_lib.sam_corpus_find(corpus._h, state, token, C.byref(t)))
     return t.value
+
+
+def sam_corpus_build_topk(corpus: Corpus, k: int) -> None:
+    _check(_lib.sam_corpus_build_topk(corpus._h, k))
+    corpus.top_k = k
+
+
+def sam_corpus_export_topk(corpus: Corpus):
+    """-> (freq uint64 [n], token int32 [n,k], target int32 [n,k], prob float32 [n,k])."""
+    n, k = sam_corpus_info(corpus)[0], corpus.top_k
+    freq = np.empty(n, dtype=np.uint64)
+    tok = np.empty((n, k), dtype=np.int32)
+    dst = np.empty((n, k), dtype=np.int32)
+    prob = np.empty((n, k), dtype=np.float32)
+    _check(_lib.sam_corpus_export_topk(corpus._h, *[x.ctypes.data_as(C.c_void_p)
+                                                    for x in (freq, tok, dst, prob)]))
+    return freq, tok, dst, prob
+
+
+def sam_batch_tree_draft(batch: Batch, max_size: int, tokens, parents, probs, sizes,
+                         stream=None) -> None:
+    import torch
+    for name, t in (("tokens", tokens), ("parents", parents), ("probs", probs)):
+        if t.numel() != batch.batch * max_size:
+            raise ValueError("%s must hold batch * max_size values" % name)
+    if sizes.numel() != batch.batch:
+        raise ValueError("sizes must hold batch values")
+    _check(_lib.sam_batch_tree_draft(batch._h, max_size, _dev_ptr(tokens, torch.int32, "tokens"),
+                                     _dev_ptr(parents, torch.int32, "parents"),
+                                     _dev_ptr(probs, torch.float32, "probs"),
+                                     _dev_ptr(sizes, torch.int32, "sizes"), _stream_ptr(stream)))
 
 
 def sam_batch_init(corpus, prompt_tokens, prompt_offsets, batch: int, vocab: int,

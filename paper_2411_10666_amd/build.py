@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsam_hip.so")
-SOURCES = ["sam_api.hip", "sam_kernels.hip", "sam_host.cpp"]
+SOURCES = ["sam_api.hip", "sam_kernels.hip", "sam_tree.hip", "sam_host.cpp"]
 HEADERS = ["sam_layout.h", "sam_device.h", "sam_host.h", os.path.join("..", "..", "include", "sam.h")]
 
 HIPCC_FLAGS = [

@@ -49,6 +49,7 @@ struct sam_corpus {
     int        device = -1;
     StaticView view = {};
     void      *d_text = nullptr, *d_linkrec = nullptr, *d_root = nullptr, *d_slots = nullptr;
+    void      *d_topk = nullptr;
     int64_t    device_bytes = 0;
 };
 
@@ -68,7 +69,8 @@ static void corpus_release_device(sam_corpus *c)
     if (c->d_linkrec) (void)hipFree(c->d_linkrec);
     if (c->d_root) (void)hipFree(c->d_root);
     if (c->d_slots) (void)hipFree(c->d_slots);
-    c->d_text = c->d_linkrec = c->d_root = c->d_slots = nullptr;
+    if (c->d_topk) (void)hipFree(c->d_topk);
+    c->d_text = c->d_linkrec = c->d_root = c->d_slots = c->d_topk = nullptr;
 }
 
 static int corpus_upload(sam_corpus *c)
@@ -177,6 +179,59 @@ int sam_corpus_find(const sam_corpus *c, int64_t state, int32_t token, int64_t *
         return fail(SAM_EINVAL, "sam_corpus_find: state or token out of range");
     const uint32_t d = c->host.find((uint32_t)state, (uint32_t)token);
     *target = d == kNil ? -1 : (int64_t)d;
+    return SAM_OK;
+}
+
+int sam_corpus_build_topk(sam_corpus *c, int32_t k)
+{
+    if (!c) return fail(SAM_EINVAL, "sam_corpus_build_topk: corpus is NULL");
+    std::string err;
+    int rc;
+    try {
+        rc = c->host.build_topk(k, err, g_progress, g_progress_user);
+    } catch (const std::bad_alloc &) {
+        rc = SAM_ENOMEM;
+        err = "sam_corpus_build_topk: out of host memory";
+    }
+    if (rc != SAM_OK) return fail(rc, err);
+    if (c->on_device) {
+        int dev = -1;
+        HIP_TRY(hipGetDevice(&dev));
+        if (dev != c->device)
+            return fail(SAM_EINVAL, "sam_corpus_build_topk: the corpus lives on another device");
+        const size_t bytes = c->host.topk.size() * sizeof(TopEnt);
+        HIP_TRY(hipDeviceSynchronize());     // no launch may still read the old table
+        if (c->d_topk) {
+            c->device_bytes -= (int64_t)((size_t)c->host.n_states * c->view.top_k * sizeof(TopEnt));
+            (void)hipFree(c->d_topk);
+            c->d_topk = nullptr;
+            c->view.topk = nullptr;
+            c->view.top_k = 0;
+        }
+        HIP_TRY(hipMalloc(&c->d_topk, bytes));
+        HIP_TRY(hipMemcpy(c->d_topk, c->host.topk.data(), bytes, hipMemcpyHostToDevice));
+        c->view.topk = (const TopEnt *)c->d_topk;
+        c->view.top_k = k;
+        c->device_bytes += (int64_t)bytes;
+    }
+    return SAM_OK;
+}
+
+int sam_corpus_export_topk(const sam_corpus *c, uint64_t *freq, int32_t *token, int32_t *target,
+                           float *prob)
+{
+    if (!c) return fail(SAM_EINVAL, "sam_corpus_export_topk: corpus is NULL");
+    const HostSam &h = c->host;
+    if (h.top_k < 1) return fail(SAM_EINVAL, "sam_corpus_export_topk: no top-k table was built");
+    const size_t n = (size_t)h.n_states * h.top_k;
+    if (freq)
+        for (uint32_t s = 0; s < h.n_states; s++) freq[s] = h.freq[s];
+    for (size_t i = 0; i < n; i++) {
+        const TopEnt &e = h.topk[i];
+        if (token) token[i] = e.dst ? (int32_t)e.token : -1;
+        if (target) target[i] = e.dst ? (int32_t)e.dst : -1;
+        if (prob) prob[i] = e.prob;
+    }
     return SAM_OK;
 }
 
@@ -313,6 +368,24 @@ int sam_batch_step(sam_batch *bt, const int32_t *accepted, const int32_t *counts
     hipError_t e = launch_feed(S, bt->view, nullptr, bt->view.batch, accepted, nullptr, counts,
                                match_len, draft, draft_len, source, (hipStream_t)hip_stream);
     if (e != hipSuccess) return fail_hip("sam_batch_step: launch", e);
+    return SAM_OK;
+}
+
+int sam_batch_tree_draft(sam_batch *bt, int32_t max_size, int32_t *tokens, int32_t *parents,
+                         float *probs, int32_t *sizes, void *hip_stream)
+{
+    if (!bt) return fail(SAM_EINVAL, "sam_batch_tree_draft: batch is NULL");
+    if (!tokens || !parents || !probs || !sizes)
+        return fail(SAM_EINVAL, "sam_batch_tree_draft: NULL buffer");
+    if (!bt->corpus || !bt->corpus->view.topk)
+        return fail(SAM_EINVAL, "sam_batch_tree_draft: the batch has no corpus with a top-k "
+                                "table (sam_corpus_build_topk)");
+    if (max_size < 1 || max_size > kMaxTreeSize)
+        return fail(SAM_EINVAL, "sam_batch_tree_draft: max_size must be in 1 .. " +
+                                    std::to_string(kMaxTreeSize));
+    hipError_t e = launch_tree(bt->corpus->view, bt->view, max_size, tokens, parents, probs,
+                               sizes, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail_hip("sam_batch_tree_draft: launch", e);
     return SAM_OK;
 }
 

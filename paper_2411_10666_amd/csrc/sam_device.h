@@ -21,6 +21,8 @@ struct StaticView {
     uint64_t       n_buckets;
     uint32_t       n_tokens;
     uint32_t       n_states;
+    const TopEnt  *topk;       // [n_states * top_k], NULL until sam_corpus_build_topk
+    int32_t        top_k;
 };
 
 // A batch of sequences: per-sequence regions are laid out back to back.
@@ -53,6 +55,9 @@ hipError_t launch_feed(const StaticView &S, const BatchView &B, const int32_t *s
 // are cleared by the caller).  Otherwise: the listed sequences, slot tables included.
 hipError_t launch_reset(const BatchView &B, const int32_t *seq_map, int n_seqs,
                         hipStream_t stream);
+// Best-first tree drafts from the static cursor of every sequence (Algorithm 4).
+hipError_t launch_tree(const StaticView &S, const BatchView &B, int max_size, int32_t *tokens,
+                       int32_t *parents, float *probs, int32_t *sizes, hipStream_t stream);
 hipError_t launch_debug(const BatchView &B, int32_t *s1, int32_t *l1, int32_t *s2, int32_t *l2,
                         int32_t *text_len, int32_t *n_states, int32_t *n_trans,
                         hipStream_t stream);

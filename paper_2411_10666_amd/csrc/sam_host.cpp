@@ -194,6 +194,74 @@ int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string
     return SAM_OK;
 }
 
+// Algorithm 3 without recursion and without per-state transition lists: a
+// transition p -> q always has len(q) > len(p), so when the transitions are
+// taken in order of decreasing len(p), freq(q) is final by the time it is added
+// to freq(p).  freq starts at 1 for states made by expansion, 0 for clones (and
+// for the root); a state is a clone iff its length differs from its min_endpos.
+int HostSam::build_topk(int k, std::string &err, ProgressFn progress, void *user)
+{
+    if (k < 1 || k > kMaxTopK) {
+        err = "sam_corpus_build_topk: k must be in 1 .. " + std::to_string(kMaxTopK);
+        return SAM_EINVAL;
+    }
+    const uint64_t n_slots = n_buckets * kBucketSlots;
+    std::vector<uint32_t> order;      // used slots, by decreasing length of the source state
+    std::vector<uint64_t> start;      // counting sort over lengths 0 .. n_tokens
+    std::vector<uint64_t> topf;       // freq of the entries of topk, while selecting
+    try {
+        freq.assign(n_states, 0);
+        topk.assign((size_t)n_states * k, TopEnt{0, 0, 0.0f});
+        topf.assign((size_t)n_states * k, 0);
+        start.assign((size_t)n_tokens + 2, 0);
+        order.resize(n_trans);
+    } catch (const std::bad_alloc &) {
+        err = "sam_corpus_build_topk: out of host memory";
+        return SAM_ENOMEM;
+    }
+    for (uint32_t s = 1; s < n_states; s++) freq[s] = len[s] == endpos[s] ? 1 : 0;
+    if (progress) progress("topk-sort", 0, 3, user);
+    uint64_t used = 0;
+    for (uint64_t j = 0; j < n_slots; j++)
+        if (slots[j].state != kNil) { start[len[slots[j].state] + 1]++; used++; }
+    for (size_t l = 1; l < start.size(); l++) start[l] += start[l - 1];
+    for (uint64_t j = 0; j < n_slots; j++)
+        if (slots[j].state != kNil) order[start[len[slots[j].state]]++] = (uint32_t)j;
+    if (progress) progress("topk-freq", 1, 3, user);
+    for (uint64_t i = used; i-- > 0;) {
+        const Slot &e = slots[order[i]];
+        freq[e.state] += freq[e.dst];
+    }
+    for (int32_t t = 0; t < vocab; t++)
+        if (root[t].dst) freq[0] += freq[root[t].dst];
+    if (progress) progress("topk-select", 2, 3, user);
+    // keep the k best successors of each state by (freq desc, token asc)
+    auto offer = [&](uint32_t state, uint32_t token, uint32_t dst) {
+        TopEnt *e = &topk[(size_t)state * k];
+        uint64_t *f = &topf[(size_t)state * k];
+        const uint64_t fd = freq[dst];
+        int pos = k;
+        while (pos > 0 && (e[pos - 1].dst == 0 || fd > f[pos - 1] ||
+                           (fd == f[pos - 1] && token < e[pos - 1].token)))
+            pos--;
+        if (pos == k) return;
+        for (int i = k - 1; i > pos; i--) { e[i] = e[i - 1]; f[i] = f[i - 1]; }
+        e[pos] = TopEnt{token, dst, 0.0f};
+        f[pos] = fd;
+    };
+    for (uint64_t j = 0; j < n_slots; j++)
+        if (slots[j].state != kNil) offer(slots[j].state, slots[j].token, slots[j].dst);
+    for (int32_t t = 0; t < vocab; t++)
+        if (root[t].dst) offer(0, (uint32_t)t, root[t].dst);
+    for (uint32_t s = 0; s < n_states; s++)
+        for (int i = 0; i < k; i++) {
+            TopEnt &e = topk[(size_t)s * k + i];
+            if (e.dst) e.prob = (float)((double)topf[(size_t)s * k + i] / (double)freq[s]);
+        }
+    top_k = k;
+    return SAM_OK;
+}
+
 uint32_t HostSam::find(uint32_t state, uint32_t token) const
 {
     if (state >= n_states || token >= (uint32_t)vocab) return kNil;

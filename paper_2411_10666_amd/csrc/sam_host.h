@@ -58,6 +58,13 @@ struct HostSam {
     // next(state)[token] or kNil
     uint32_t find(uint32_t state, uint32_t token) const;
 
+    // Algorithm 3: freq per state, the k most frequent successors of every state
+    // and their probabilities.  Fills freq and topk (n_states * k entries).
+    int top_k = 0;
+    std::vector<uint64_t> freq;
+    std::vector<TopEnt>   topk;
+    int build_topk(int k, std::string &err, ProgressFn progress = nullptr, void *user = nullptr);
+
     // {link, length(link)} per state, for the device
     void make_linkrec(std::vector<LinkRec> &out) const;
 

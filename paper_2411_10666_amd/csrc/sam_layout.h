@@ -11,6 +11,8 @@
 //                            open addressing, 128-byte buckets of 8 slots,
 //                            linear over buckets; root's transitions are not
 //                            in it (they are in root[]).
+//    topk[n_states * k]      {token, target, probability}, optional     12 B
+//                            (Algorithm 3; only for tree drafts)
 //
 //  dynamic automaton (one private region per sequence), two layouts:
 //    text[max_seq_len]       int32
@@ -52,6 +54,15 @@ struct RootEnt {         // 8 B, static automaton; dst == 0 means no transition
     uint32_t dst;
     uint32_t endpos;
 };
+
+struct TopEnt {          // 12 B, static automaton, k per state; dst == 0 means unused
+    uint32_t token;
+    uint32_t dst;
+    float    prob;       // freq(dst) / freq(state)
+};
+
+constexpr int kMaxTopK = 8;
+constexpr int kMaxTreeSize = 128;
 
 struct DynRec {          // 32 B, dynamic automaton
     uint32_t len;

@@ -86,3 +86,31 @@ def test_argument_errors():
     assert lib.sam_batch_status(None, None, None) == sam.SAM_EINVAL
     lib.sam_corpus_free(None)
     lib.sam_batch_free(None)
+
+
+@pytest.mark.parametrize("seed,k", [(0, 1), (1, 2), (2, 3), (3, 4), (4, 8)])
+def test_host_topk_matches_checker(seed, k):
+    """Algorithm 3 in the library (edge-ordered, no recursion) against the checker's dfs."""
+    rng = np.random.default_rng(900 + seed)
+    vocab = [2, 3, 5, 9, 40][seed]
+    x = rng.integers(0, vocab, size=int(rng.integers(5, 500))).astype(np.int32)
+    c = sam.sam_build_host_only(x, vocab)
+    sam.sam_corpus_build_topk(c, k)
+    ref = Sam.build(x)
+    ref.init_topk(k)
+    for got, want in zip(sam.sam_corpus_export_topk(c), ref.topk()):
+        assert got.dtype == want.dtype and np.array_equal(got, want)
+
+
+def test_host_topk_cfg1_corpus():
+    spec = CONFIGS["cfg1"]
+    x = make_corpus(spec)
+    c = sam.sam_build_host_only(x, spec.vocab)
+    sam.sam_corpus_build_topk(c, 4)
+    ref = Sam.build(x)
+    ref.init_topk(4)
+    for got, want in zip(sam.sam_corpus_export_topk(c), ref.topk()):
+        assert np.array_equal(got, want)
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_corpus_build_topk(c, 9)
+    assert e.value.code == sam.SAM_EINVAL

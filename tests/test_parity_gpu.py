@@ -217,6 +217,71 @@ def test_auxiliary_threshold_hook(l_threshold, l_bias):
         assert (srcs == 3).any()
 
 
+@pytest.mark.parametrize("seed,vocab,k,max_size", [(60, 2, 2, 40), (61, 3, 3, 16), (62, 6, 4, 70),
+                                                   (63, 32000, 4, 40), (64, 3, 8, 128), (65, 4, 1, 5)])
+def test_tree_draft_matches_checker(seed, vocab, k, max_size):
+    """Algorithm 4 on the GPU against the checker: tokens, parents, probability bits."""
+    import torch
+    from oracle.sam_oracle import Sam, Sequence
+    from paper_2411_10666_amd import binding as sam
+    dev = torch.device("cuda:0")
+    B, T, A, L, steps = 10, 200, 6, 4, 12
+    _say("tree draft seed=%d vocab=%d k=%d max_size=%d" % (seed, vocab, k, max_size))
+    corpus, prompts, acc, counts = _random_case(seed, vocab, 3000, B, T, A, L, steps)
+    prompts[0] = np.zeros(0, np.int32)
+    counts[:, 0] = 0                                  # one sequence stays empty: size 0
+    st = Sam.build(corpus)
+    st.init_topk(k)
+    gc = sam.sam_build(corpus, vocab)
+    sam.sam_corpus_build_topk(gc, k)
+    for got, want in zip(sam.sam_corpus_export_topk(gc), st.topk()):
+        assert np.array_equal(got, want)
+    offs = np.zeros(B + 1, np.int64); offs[1:] = np.cumsum([len(p) for p in prompts])
+    batch = sam.sam_batch_init(gc, torch.from_numpy(np.concatenate(prompts)).to(dev),
+                               torch.from_numpy(offs).to(dev), B, vocab, T, A, L)
+    seqs = [Sequence(st, corpus) for _ in range(B)]
+    last = [-1] * B
+    for b, p in enumerate(prompts):
+        seqs[b].feed(p)
+        if len(p):
+            last[b] = int(p[-1])
+    i32 = dict(dtype=torch.int32, device=dev)
+    ml = torch.empty(B, **i32); dl = torch.empty(B, **i32); src = torch.empty(B, **i32)
+    dr = torch.empty(B, L, **i32)
+    tt = torch.empty(B, max_size, **i32); tp = torch.empty(B, max_size, **i32)
+    tpr = torch.empty(B, max_size, dtype=torch.float32, device=dev); ts = torch.empty(B, **i32)
+    for s in range(steps):
+        sam.sam_batch_step(batch, torch.from_numpy(acc[s]).to(dev), torch.from_numpy(counts[s]).to(dev),
+                           ml, dr, dl, src)
+        sam.sam_batch_tree_draft(batch, max_size, tt, tp, tpr, ts)
+        torch.cuda.synchronize()
+        gt, gp, gpr, gs = tt.cpu().numpy(), tp.cpu().numpy(), tpr.cpu().numpy(), ts.cpu().numpy()
+        for b in range(B):
+            seqs[b].feed(acc[s, b, :counts[s, b]])
+            if counts[s, b]:
+                last[b] = int(acc[s, b, counts[s, b] - 1])
+            if last[b] < 0:
+                assert gs[b] == 0 and (gt[b] == -1).all()
+                continue
+            wt, wp, wpr = st.prim(seqs[b].cursors()[0], last[b], max_size)
+            n = len(wt)
+            assert gs[b] == n, (s, b)
+            assert np.array_equal(gt[b, :n], wt) and np.array_equal(gp[b, :n], wp), (s, b)
+            assert np.array_equal(gpr[b, :n].view(np.uint32), wpr.view(np.uint32)), (s, b)
+            assert (gt[b, n:] == -1).all() and (gp[b, n:] == -1).all() and (gpr[b, n:] == 0).all()
+    # no table, bad size
+    plain = sam.sam_build(corpus, vocab)
+    b2 = sam.sam_batch_init(plain, torch.from_numpy(np.concatenate(prompts)).to(dev),
+                            torch.from_numpy(offs).to(dev), B, vocab, T, A, L)
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_batch_tree_draft(b2, max_size, tt, tp, tpr, ts)
+    assert e.value.code == sam.SAM_EINVAL
+    big = torch.empty(B, 129, **i32)
+    with pytest.raises(sam.SamError) as e:
+        sam.sam_batch_tree_draft(batch, 129, big, big, torch.empty(B, 129, device=dev), ts)
+    assert e.value.code == sam.SAM_EINVAL
+
+
 def test_reset_recycles_sequences():
     """Continuous batching: some sequences are replaced by new requests in the
     middle of a run; the others carry on untouched."""
