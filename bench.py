@@ -78,7 +78,7 @@ def _log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def gpu_leg(w, steps, warmup):
+def gpu_leg(w, steps, warmup, tree=None):
     import torch
     from paper_2411_10666_amd import binding as sam
 
@@ -163,7 +163,37 @@ def gpu_leg(w, steps, warmup):
         raise RuntimeError("device status word is %d after the timed steps" % status)
     if timed_draft_tokens <= 0:
         raise RuntimeError("no draft tokens were produced")
-    return dict(wall_s=wall, event_ms=ev_ms, match_steps=timed_match_steps,
+    tree_out = None
+    if tree and corpus is not None:
+        # Tree drafts (Algorithms 3 and 4) from the state the timed steps ended in;
+        # reported beside the main metric, not part of it.
+        k, max_size = tree
+        t = time.time()
+        sam.sam_corpus_build_topk(corpus, k)
+        topk_s = time.time() - t
+        tt = torch.empty(B, max_size, **i32)
+        tp = torch.empty(B, max_size, **i32)
+        tpr = torch.empty(B, max_size, dtype=torch.float32, device=dev)
+        ts = torch.empty(B, **i32)
+        for _ in range(20):
+            sam.sam_batch_tree_draft(batch, max_size, tt, tp, tpr, ts, stream)
+        torch.cuda.synchronize()
+        calls = 500
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(calls):
+            sam.sam_batch_tree_draft(batch, max_size, tt, tp, tpr, ts, stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / calls
+        entries = int(ts.sum().item())
+        tree_out = {"k": k, "max_size": max_size, "ms_per_call": ms,
+                    "entries_per_call": entries, "entries_per_s": entries / (ms * 1e-3),
+                    "topk_build_s": topk_s,
+                    # per entry: one k x 12 B table read and 12 B of output
+                    "algo_gbps": entries * (12.0 * k + 12.0) / (ms * 1e-3) / 1e9}
+    return dict(tree=tree_out, wall_s=wall, event_ms=ev_ms, match_steps=timed_match_steps,
                 draft_tokens=timed_draft_tokens, init_s=init_s, build_s=build_s,
                 states=info[0], trans=info[1], static_bytes=info[2],
                 batch_bytes=sam.sam_batch_info(batch))
@@ -205,6 +235,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", default="cfg2", choices=sorted(CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tree-draft", default="",
+                    help="K,MAX_SIZE: also time sam_batch_tree_draft (reported as tree_draft)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB before the timed "
                          "steps (a kernel of known traffic to scale profiler counters by)")
@@ -235,7 +267,8 @@ def main():
         _log("copy probe: %d MiB read + %d MiB written by one copy kernel"
              % (args.copy_probe_mib, args.copy_probe_mib))
         del src_t, dst_t
-    g = gpu_leg(w, args.steps, args.warmup)
+    tree = tuple(int(v) for v in args.tree_draft.split(",")) if args.tree_draft else None
+    g = gpu_leg(w, args.steps, args.warmup, tree)
 
     per_step_ms = g["event_ms"] / args.steps
     value = g["match_steps"] / (g["event_ms"] * 1e-3)
@@ -284,6 +317,8 @@ def main():
             "avg_launch_ms": per_step_ms,
         },
     }
+    if g["tree"]:
+        out["tree_draft"] = g["tree"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_leg(w)
     print(json.dumps(out), flush=True)
