@@ -121,6 +121,43 @@ def test_long_rows_and_wide_drafts():
     assert_same(g, r)
 
 
+def test_maximum_row_and_draft_sizes():
+    """max_accept and draft_len at the largest values the library accepts."""
+    B, T, A, L, steps, vocab = 3, 9000, 4096, 1024, 3, 3
+    _say("maximum sizes A=%d L=%d" % (A, L))
+    rng = np.random.default_rng(90)
+    corpus = rng.integers(0, vocab, size=4000).astype(np.int32)
+    prompts = [rng.integers(0, vocab, size=n).astype(np.int32) for n in (0, 100, 700)]
+    acc = rng.integers(0, vocab, size=(steps, B, A)).astype(np.int32)
+    acc[1, 1, :3000] = np.tile(corpus[100:1100], 3)      # long copies: long static matches
+    counts = np.array([[4096, 1, 17], [0, 3000, 4096], [2000, 4096, 64]], dtype=np.int32)
+    g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r)
+    assert max(int(x["draft_len"].max()) for x in r) == L
+
+
+@pytest.mark.parametrize("T", [16366, 16367])
+def test_layout_switch_at_the_compact_limit(T):
+    """max_seq_len 16366 is the last compact-layout size, 16367 the first wide one;
+    one sequence is filled to the very end (state ids reach 2T)."""
+    B, A, L, vocab = 2, 4096, 8, 2
+    _say("layout limit T=%d" % T)
+    rng = np.random.default_rng(91)
+    corpus = rng.integers(0, vocab, size=1000).astype(np.int32)
+    prompts = [rng.integers(0, vocab, size=T - 3 * 4096).astype(np.int32),
+               np.zeros(10, np.int32)]
+    acc = rng.integers(0, vocab, size=(3, B, A)).astype(np.int32)
+    acc[:, 1] = 0                                          # one token repeated
+    counts = np.array([[4096, 4096]] * 3, dtype=np.int32)
+    g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r)
+    assert g[-1]["sizes"][0, 0] == T
+
+
 def test_single_token_sequences_fill_to_capacity():
     """Sequences grown exactly to max_seq_len (the worst-case table sizes), one
     repeated token and a two-token alternation included."""
