@@ -52,7 +52,7 @@ MEASURED_TRAFFIC = {
     # (176.65 x 2.0 + 40.46 x 1.0) KiB: FETCH_SIZE / WRITE_SIZE means over the 484
     # step launches of one schedule pass; the same counters read 131088.6 and
     # 262144.0 for a copy kernel that reads and writes 262144 KiB
-    "cfg2": {"bytes_per_launch": 403200.0, "sources": "8a372325e7acf98d"},
+    "cfg2": {"bytes_per_launch": 403200.0, "sources": "71356db87764ddee"},
 }
 
 KERNEL_SOURCES = ["sam_kernels.hip", "sam_layout.h", "sam_device.h"]
