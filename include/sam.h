@@ -100,6 +100,22 @@ int sam_set_progress_callback(sam_progress_fn fn, void *user);
 int sam_build_host_only(const int32_t *corpus_tokens, int64_t n_tokens, int32_t vocab,
                         sam_corpus **out);
 
+/*
+ * Write a built corpus automaton to a file, and read one back instead of
+ * building it (a 500 M-token corpus takes minutes to build).  The file holds the
+ * host arrays as raw bytes behind a 64-byte header; it is valid for this library
+ * layout version on a machine of the same byte order.  The top-k table is not
+ * stored (sam_corpus_build_topk recomputes it).  sam_corpus_load copies the
+ * automaton to the current device like sam_build; _host_only does not.  Loading
+ * verifies the header, the file length and the consistency of every state and
+ * transition, so a damaged file is refused.
+ * Errors: SAM_EINVAL (cannot open, not such a file, damaged), SAM_ENOMEM,
+ * SAM_EDEVICE.
+ */
+int sam_corpus_save(const sam_corpus *corpus, const char *path);
+int sam_corpus_load(const char *path, sam_corpus **out);
+int sam_corpus_load_host_only(const char *path, sam_corpus **out);
+
 /* Counts of the built automaton and bytes of device memory it occupies
  * (0 for a host-only handle).  Any output pointer may be NULL. */
 int sam_corpus_info(const sam_corpus *corpus, int64_t *n_states, int64_t *n_trans,

@@ -26,7 +26,7 @@ EXPORTS = [
     "sam_batch_info", "sam_batch_free", "sam_set_layout_override",
     "sam_batch_reset", "sam_set_progress_callback",
     "sam_batch_set_threshold", "sam_corpus_build_topk", "sam_corpus_export_topk",
-    "sam_batch_tree_draft",
+    "sam_batch_tree_draft", "sam_corpus_save", "sam_corpus_load", "sam_corpus_load_host_only",
 ]
 
 
@@ -63,6 +63,9 @@ def _load():
     L.sam_set_progress_callback.argtypes = [PROGRESS_FN, vp]
     L.sam_batch_set_threshold.argtypes = [vp, i32]
     L.sam_corpus_build_topk.argtypes = [vp, i32]
+    L.sam_corpus_save.argtypes = [vp, C.c_char_p]
+    L.sam_corpus_load.argtypes = [C.c_char_p, C.POINTER(vp)]
+    L.sam_corpus_load_host_only.argtypes = [C.c_char_p, C.POINTER(vp)]
     L.sam_corpus_export_topk.argtypes = [vp, vp, vp, vp, vp]
     L.sam_batch_tree_draft.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     L.sam_batch_reset.argtypes = [vp, vp, i32, vp, vp, vp]
@@ -152,6 +155,22 @@ def sam_build_host_only(corpus_tokens, vocab: int) -> Corpus:
     a, p = _host_tokens(corpus_tokens)
     h = C.c_void_p()
     _check(_lib.sam_build_host_only(p, a.size, vocab, C.byref(h)))
+    return Corpus(h)
+
+
+def sam_corpus_save(corpus: Corpus, path: str) -> None:
+    _check(_lib.sam_corpus_save(corpus._h, os.fsencode(path)))
+
+
+def sam_corpus_load(path: str) -> Corpus:
+    h = C.c_void_p()
+    _check(_lib.sam_corpus_load(os.fsencode(path), C.byref(h)))
+    return Corpus(h)
+
+
+def sam_corpus_load_host_only(path: str) -> Corpus:
+    h = C.c_void_p()
+    _check(_lib.sam_corpus_load_host_only(os.fsencode(path), C.byref(h)))
     return Corpus(h)
 
 

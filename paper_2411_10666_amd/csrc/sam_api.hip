@@ -150,6 +150,51 @@ int sam_build_host_only(const int32_t *corpus_tokens, int64_t n_tokens, int32_t 
     return build_common(corpus_tokens, n_tokens, vocab, false, out);
 }
 
+int sam_corpus_save(const sam_corpus *c, const char *path)
+{
+    if (!c || !path) return fail(SAM_EINVAL, "sam_corpus_save: NULL argument");
+    std::string err;
+    const int rc = c->host.save(path, err);
+    return rc == SAM_OK ? SAM_OK : fail(rc, err);
+}
+
+static int load_common(const char *path, bool upload, sam_corpus **out)
+{
+    if (!out || !path) return fail(SAM_EINVAL, "sam_corpus_load: NULL argument");
+    *out = nullptr;
+    sam_corpus *c = new (std::nothrow) sam_corpus;
+    if (!c) return fail(SAM_ENOMEM, "sam_corpus_load: out of host memory");
+    std::string err;
+    int rc;
+    try {
+        rc = c->host.load(path, err);
+    } catch (const std::bad_alloc &) {
+        rc = SAM_ENOMEM;
+        err = "sam_corpus_load: out of host memory";
+    }
+    if (rc != SAM_OK) {
+        delete c;
+        return fail(rc, err);
+    }
+    if (upload) {
+        rc = corpus_upload(c);
+        if (rc != SAM_OK) {
+            corpus_release_device(c);
+            delete c;
+            return rc;
+        }
+    }
+    *out = c;
+    return SAM_OK;
+}
+
+int sam_corpus_load(const char *path, sam_corpus **out) { return load_common(path, true, out); }
+
+int sam_corpus_load_host_only(const char *path, sam_corpus **out)
+{
+    return load_common(path, false, out);
+}
+
 int sam_corpus_info(const sam_corpus *c, int64_t *n_states, int64_t *n_trans,
                     int64_t *device_bytes)
 {

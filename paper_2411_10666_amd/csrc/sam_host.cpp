@@ -6,6 +6,7 @@
 // with min_endpos(target), which is what the device wants there.
 #include "sam_host.h"
 
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 #include <sys/mman.h>
@@ -259,6 +260,159 @@ int HostSam::build_topk(int k, std::string &err, ProgressFn progress, void *user
             if (e.dst) e.prob = (float)((double)topf[(size_t)s * k + i] / (double)freq[s]);
         }
     top_k = k;
+    return SAM_OK;
+}
+
+// ---- file format -----------------------------------------------------------
+// header (64 bytes): magic "SAMCORP1", layout version, bucket width, n_tokens,
+// vocab, n_states, n_trans, n_buckets; then the arrays in the order text, len,
+// link, endpos, root, slots, each as raw bytes.
+
+namespace {
+
+struct FileHeader {
+    char     magic[8];
+    uint32_t version;
+    uint32_t bucket_slots;
+    int64_t  n_tokens;
+    int64_t  vocab;
+    uint64_t n_states;
+    uint64_t n_trans;
+    uint64_t n_buckets;
+    uint64_t reserved;
+};
+static_assert(sizeof(FileHeader) == 64, "file header is 64 bytes");
+constexpr char kMagic[8] = {'S', 'A', 'M', 'C', 'O', 'R', 'P', '1'};
+constexpr uint32_t kFileVersion = 1;
+
+bool write_all(FILE *f, const void *p, size_t bytes)
+{
+    const char *c = (const char *)p;
+    while (bytes) {
+        const size_t chunk = bytes < ((size_t)1 << 30) ? bytes : ((size_t)1 << 30);
+        if (fwrite(c, 1, chunk, f) != chunk) return false;
+        c += chunk;
+        bytes -= chunk;
+    }
+    return true;
+}
+
+bool read_all(FILE *f, void *p, size_t bytes)
+{
+    char *c = (char *)p;
+    while (bytes) {
+        const size_t chunk = bytes < ((size_t)1 << 30) ? bytes : ((size_t)1 << 30);
+        if (fread(c, 1, chunk, f) != chunk) return false;
+        c += chunk;
+        bytes -= chunk;
+    }
+    return true;
+}
+
+}  // namespace
+
+int HostSam::save(const char *path, std::string &err) const
+{
+    FILE *f = fopen(path, "wb");
+    if (!f) { err = std::string("sam_corpus_save: cannot open ") + path; return SAM_EINVAL; }
+    FileHeader h = {};
+    memcpy(h.magic, kMagic, 8);
+    h.version = kFileVersion;
+    h.bucket_slots = kBucketSlots;
+    h.n_tokens = n_tokens; h.vocab = vocab; h.n_states = n_states; h.n_trans = n_trans;
+    h.n_buckets = n_buckets;
+    const bool ok = write_all(f, &h, sizeof(h)) &&
+                    write_all(f, text.data(), (size_t)n_tokens * sizeof(int32_t)) &&
+                    write_all(f, len.data(), (size_t)n_states * sizeof(uint32_t)) &&
+                    write_all(f, link.data(), (size_t)n_states * sizeof(uint32_t)) &&
+                    write_all(f, endpos.data(), (size_t)n_states * sizeof(uint32_t)) &&
+                    write_all(f, root.data(), (size_t)vocab * sizeof(RootEnt)) &&
+                    write_all(f, slots, (size_t)n_buckets * kBucketSlots * sizeof(Slot));
+    const bool closed = fclose(f) == 0;
+    if (!ok || !closed) { err = std::string("sam_corpus_save: write failed on ") + path; return SAM_EINVAL; }
+    return SAM_OK;
+}
+
+int HostSam::load(const char *path, std::string &err)
+{
+    FILE *f = fopen(path, "rb");
+    if (!f) { err = std::string("sam_corpus_load: cannot open ") + path; return SAM_EINVAL; }
+    FileHeader h;
+    int rc = SAM_OK;
+    if (!read_all(f, &h, sizeof(h)) || memcmp(h.magic, kMagic, 8) != 0 ||
+        h.version != kFileVersion || h.bucket_slots != (uint32_t)kBucketSlots) {
+        err = std::string("sam_corpus_load: ") + path + " is not an automaton file of this library version";
+        rc = SAM_EINVAL;
+    } else if (h.n_tokens < 1 || h.n_tokens > 0x7FFFFFFELL || h.vocab < 1 || h.vocab > 0x7FFFFFFFLL ||
+               h.n_states < 2 || h.n_states > 2 * (uint64_t)h.n_tokens + 1 ||
+               h.n_buckets != static_buckets_for(h.n_tokens)) {
+        err = std::string("sam_corpus_load: inconsistent header in ") + path;
+        rc = SAM_EINVAL;
+    }
+    if (rc == SAM_OK) {
+        n_tokens = h.n_tokens; vocab = (int32_t)h.vocab; n_states = (uint32_t)h.n_states;
+        n_trans = h.n_trans; n_buckets = h.n_buckets;
+        const size_t n_slots = (size_t)n_buckets * kBucketSlots;
+        try {
+            text.resize((size_t)n_tokens);
+            root.resize((size_t)vocab);
+        } catch (const std::bad_alloc &) {
+            rc = SAM_ENOMEM;
+        }
+        free(slots);
+        slots = nullptr;
+        if (rc == SAM_OK && (!len.reserve(n_states) || !link.reserve(n_states) ||
+                             !endpos.reserve(n_states) ||
+                             !(slots = (Slot *)huge_alloc(n_slots * sizeof(Slot)))))
+            rc = SAM_ENOMEM;
+        if (rc != SAM_OK) {
+            err = "sam_corpus_load: out of host memory";
+        } else {
+            len.set_size(n_states); link.set_size(n_states); endpos.set_size(n_states);
+            const bool ok = read_all(f, text.data(), (size_t)n_tokens * sizeof(int32_t)) &&
+                            read_all(f, &len[0], (size_t)n_states * sizeof(uint32_t)) &&
+                            read_all(f, &link[0], (size_t)n_states * sizeof(uint32_t)) &&
+                            read_all(f, &endpos[0], (size_t)n_states * sizeof(uint32_t)) &&
+                            read_all(f, root.data(), (size_t)vocab * sizeof(RootEnt)) &&
+                            read_all(f, slots, n_slots * sizeof(Slot));
+            char extra;
+            if (!ok || fread(&extra, 1, 1, f) != 0) {
+                err = std::string("sam_corpus_load: ") + path + " is truncated or has trailing bytes";
+                rc = SAM_EINVAL;
+            }
+        }
+    }
+    fclose(f);
+    if (rc != SAM_OK) return rc;
+    // cheap structural checks, so that a damaged file cannot send a kernel out of bounds
+    if (len[0] != 0 || link[0] != kNil) { err = "sam_corpus_load: bad root record"; return SAM_EINVAL; }
+    for (uint32_t s = 1; s < n_states; s++)
+        if (link[s] >= n_states || len[link[s]] >= len[s] || endpos[s] > (uint64_t)n_tokens ||
+            len[s] > endpos[s]) {
+            err = "sam_corpus_load: state " + std::to_string(s) + " is inconsistent";
+            return SAM_EINVAL;
+        }
+    uint64_t used = 0;
+    const uint64_t n_slots = n_buckets * kBucketSlots;
+    for (uint64_t j = 0; j < n_slots; j++)
+        if (slots[j].state != kNil) {
+            used++;
+            if (slots[j].state >= n_states || slots[j].dst == 0 || slots[j].dst >= n_states ||
+                slots[j].token >= (uint32_t)vocab || slots[j].w != endpos[slots[j].dst]) {
+                err = "sam_corpus_load: transition slot " + std::to_string(j) + " is inconsistent";
+                return SAM_EINVAL;
+            }
+        }
+    for (int32_t t = 0; t < vocab; t++)
+        if (root[t].dst) {
+            used++;
+            if (root[t].dst >= n_states || root[t].endpos != endpos[root[t].dst]) {
+                err = "sam_corpus_load: root transition " + std::to_string(t) + " is inconsistent";
+                return SAM_EINVAL;
+            }
+        }
+    if (used != n_trans) { err = "sam_corpus_load: transition count does not match"; return SAM_EINVAL; }
+    if (n_slots - (used - 0) < 1) { err = "sam_corpus_load: transition table is full"; return SAM_EINVAL; }
     return SAM_OK;
 }
 

@@ -21,6 +21,7 @@ public:
     bool reserve(size_t cap);            // false: out of memory
     void release();
     void push_back(const T &v) { p_[n_++] = v; }
+    void set_size(size_t n) { n_ = n; }  // after reserve(), before filling by index
     T &operator[](size_t i) { return p_[i]; }
     const T &operator[](size_t i) const { return p_[i]; }
     size_t size() const { return n_; }
@@ -54,6 +55,11 @@ struct HostSam {
     typedef void (*ProgressFn)(const char *phase, int64_t done, int64_t total, void *user);
     int build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string &err,
               ProgressFn progress = nullptr, void *user = nullptr);
+
+    // Write the built automaton to a file / read it back (same machine byte
+    // order, same library layout version).  The top-k table is not stored.
+    int save(const char *path, std::string &err) const;
+    int load(const char *path, std::string &err);
 
     // next(state)[token] or kNil
     uint32_t find(uint32_t state, uint32_t token) const;

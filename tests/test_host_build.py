@@ -114,3 +114,57 @@ def test_host_topk_cfg1_corpus():
     with pytest.raises(sam.SamError) as e:
         sam.sam_corpus_build_topk(c, 9)
     assert e.value.code == sam.SAM_EINVAL
+
+
+def test_save_and_load_round_trip(tmp_path):
+    rng = np.random.default_rng(5)
+    x = rng.integers(0, 7, size=5000).astype(np.int32)
+    c = sam.sam_build_host_only(x, 7)
+    path = str(tmp_path / "corpus.sam")
+    sam.sam_corpus_save(c, path)
+    d = sam.sam_corpus_load_host_only(path)
+    assert sam.sam_corpus_info(d) == sam.sam_corpus_info(c)
+    for a, b in zip(sam.sam_corpus_export(c), sam.sam_corpus_export(d)):
+        assert np.array_equal(a, b)
+    n_states = sam.sam_corpus_info(c)[0]
+    for s in rng.integers(0, n_states, size=300).tolist():
+        for t in range(7):
+            assert sam.sam_corpus_find(c, s, t) == sam.sam_corpus_find(d, s, t)
+    # the top-k table is rebuilt from a loaded automaton
+    sam.sam_corpus_build_topk(c, 3)
+    sam.sam_corpus_build_topk(d, 3)
+    for a, b in zip(sam.sam_corpus_export_topk(c), sam.sam_corpus_export_topk(d)):
+        assert np.array_equal(a, b)
+
+
+def test_load_refuses_damaged_files(tmp_path):
+    x = np.random.default_rng(6).integers(0, 5, size=800).astype(np.int32)
+    c = sam.sam_build_host_only(x, 5)
+    path = str(tmp_path / "corpus.sam")
+    sam.sam_corpus_save(c, path)
+    raw = bytearray(open(path, "rb").read())
+
+    def expect_refused(data):
+        bad = str(tmp_path / "bad.sam")
+        open(bad, "wb").write(bytes(data))
+        with pytest.raises(sam.SamError) as e:
+            sam.sam_corpus_load_host_only(bad)
+        assert e.value.code == sam.SAM_EINVAL
+
+    expect_refused(raw[:-16])                      # truncated
+    expect_refused(raw + b"x")                     # trailing bytes
+    expect_refused(b"NOTACORP" + raw[8:])          # wrong magic
+    flipped = bytearray(raw)
+    off = 64 + 4 * 800 + 4 * 3                     # length of state 3
+    flipped[off:off + 4] = (10 ** 6).to_bytes(4, "little")
+    expect_refused(flipped)
+    # a transition whose target is out of range: first used slot of the table
+    n_states = sam.sam_corpus_info(c)[0]
+    slots_at = 64 + 4 * 800 + 12 * n_states + 8 * 5
+    slots = np.frombuffer(bytes(raw[slots_at:]), dtype=np.uint32).reshape(-1, 4)
+    j = int(np.flatnonzero(slots[:, 0] != 0xFFFFFFFF)[0])
+    bad_slot = bytearray(raw)
+    bad_slot[slots_at + 16 * j + 8:slots_at + 16 * j + 12] = (4 * 10 ** 6).to_bytes(4, "little")
+    expect_refused(bad_slot)
+    with pytest.raises(sam.SamError):
+        sam.sam_corpus_load_host_only(str(tmp_path / "missing.sam"))

@@ -319,6 +319,22 @@ def test_tree_draft_matches_checker(seed, vocab, k, max_size):
     assert e.value.code == sam.SAM_EINVAL
 
 
+def test_loaded_corpus_behaves_like_a_built_one(tmp_path):
+    from paper_2411_10666_amd import binding as sam
+    B, T, A, L, steps, vocab = 6, 300, 6, 8, 25, 5
+    _say("corpus saved, loaded, used")
+    corpus, prompts, acc, counts = _random_case(70, vocab, 3000, B, T, A, L, steps)
+    built = sam.sam_build_host_only(corpus, vocab)
+    path = str(tmp_path / "c.sam")
+    sam.sam_corpus_save(built, path)
+    loaded = sam.sam_corpus_load(path)
+    assert sam.sam_corpus_info(loaded)[2] > 0
+    g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L, gpu_corpus=loaded)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r)
+
+
 def test_reset_recycles_sequences():
     """Continuous batching: some sequences are replaced by new requests in the
     middle of a run; the others carry on untouched."""
