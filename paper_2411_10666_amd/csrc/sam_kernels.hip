@@ -385,19 +385,21 @@ __device__ __forceinline__ void dyn_expand(const DynSeq &D, uint32_t t, uint32_t
     } else {
         uint32_t p = c.P;
         Rec R = c.RP;
-        Probe<L> pr;
-        if (c.pf_ok) {
-            pr = c.pf;
-        } else {
-            pr.b = dyn_bucket(D, p, t);
-            pr.sl = issue_bucket<L>(D, pr.b, lane);
-            reduce_bucket<L>(pr, p, t);
-        }
+        Probe<L> pr = c.pf;
+        bool have_pr = c.pf_ok;
         uint32_t q = kNil, where = kNil;
         // give t-transitions to the states on last's suffix path that lack one
         for (;;) {
             if (--guard == 0) { fault |= SAM_STATUS_INTERNAL_BIT; p = kNil; break; }
             if (R.itok == t) { q = R.idst; where = kInline; break; }
+            if (!have_pr) {
+                // P's bucket was not prefetched (P is a fresh clone, or this is the first
+                // token of a launch); it is only needed now that the inline transition
+                // is a different token
+                pr.b = dyn_bucket(D, p, t);
+                pr.sl = issue_bucket<L>(D, pr.b, lane);
+                reduce_bucket<L>(pr, p, t);
+            }
             uint32_t at, dst;
             if (resolve_probe<L>(D, pr, p, t, lane, at, dst)) { q = dst; where = at; break; }
             if (R.itok == kNil) {
@@ -417,6 +419,7 @@ __device__ __forceinline__ void dyn_expand(const DynSeq &D, uint32_t t, uint32_t
             if (R.link == kNil) { p = kNil; break; }   // R stays the root's record
             p = R.link;
             rec_and_probe<L>(D, p, t, lane, R, pr);
+            have_pr = true;
         }
 
         if (p == kNil) {
