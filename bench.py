@@ -34,7 +34,9 @@ HBM_PEAK_GBPS = 8000.0
 # Algorithmic bytes one match-step moves, per workload: the operation counts of
 # the method (probes, suffix-link reads, inserts, redirects, clone copies, state
 # writes, text appends) and the draft gather, each priced at the element size of
-# the device layout.  Written by oracle/count_ops.py; derivation in the design doc.
+# the device layout (16 B per probe, record read, insert, redirect and state write,
+# 32 B per copied transition, 8 B per token, 8 B per draft token, 16 B of per-sequence
+# step inputs/outputs).  Computed by oracle/count_ops.py.
 ALGO_BYTES_PER_MATCH_STEP = {
     "cfg1": 235.8,
     "cfg2": 245.1,
@@ -243,7 +245,7 @@ def main():
 
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (sequences are independent and "
+        print("bench.py: the library runs on one GPU only (sequences are independent and "
               "would be sharded without communication); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     if args.steps < 1 or args.warmup < 0:
@@ -275,7 +277,7 @@ def main():
     algo_bytes_per_launch = ALGO_BYTES_PER_MATCH_STEP[spec.name] * g["match_steps"] / args.steps
     achieved = algo_bytes_per_launch / (per_step_ms * 1e-3) / 1e9
     out = {
-        "metric": "SAM match-steps/sec (1 GPU)",
+        "metric": "SAM match-steps/sec + draft tokens/sec (1 GPU), % of HBM roofline",
         "value": value,
         "unit": "match-steps/s",
         "n_gpus": 1,

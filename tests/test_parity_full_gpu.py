@@ -3,8 +3,8 @@ pre-marshalled step plan, back-to-back launches on one stream, outputs of every
 step kept): the whole schedule of a benchmark workload is run through the HIP
 library and every output of every step is compared with the CPU checker.
 
-Progress lines go to gpurun_out/test_progress.log so a long, quiet test can be
-told from a hung one."""
+Progress lines are appended to a log file in the run's output folder (PROGRESS_DIR)
+so that a long, quiet test can be told from a hung one."""
 import os
 import time
 
@@ -16,10 +16,11 @@ from paper_2411_10666_amd.synth import CONFIGS, make_workload
 pytestmark = pytest.mark.gpu
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+PROGRESS_DIR = os.environ.get("SAM_TEST_PROGRESS_DIR", os.path.join(ROOT, "gpurun_out"))
 
 
 def _say(msg):
-    d = os.path.join(ROOT, "gpurun_out")
+    d = PROGRESS_DIR
     os.makedirs(d, exist_ok=True)
     with open(os.path.join(d, "test_progress.log"), "a") as f:
         f.write("%s %s\n" % (time.strftime("%H:%M:%S"), msg))
