@@ -121,6 +121,41 @@ def test_long_rows_and_wide_drafts():
     assert_same(g, r)
 
 
+@pytest.mark.parametrize("block", range(4))
+def test_many_random_shapes(block):
+    """Forty small workloads with random batch, capacity, row width, draft length,
+    vocabulary, bias and layout; repeated tokens and periodic texts are common at
+    these vocabulary sizes, which exercises clones, redirects and list copies."""
+    from paper_2411_10666_amd import binding as sam
+    rng = np.random.default_rng(1234 + block)
+    for case in range(10):
+        vocab = int(rng.choice([2, 2, 3, 3, 4, 6, 11]))
+        B = int(rng.integers(1, 70))
+        T = int(rng.integers(20, 400))
+        A = int(rng.integers(1, 20))
+        L = int(rng.integers(1, 40))
+        steps = int(rng.integers(3, 30))
+        n_corpus = int(rng.integers(40, 3000))
+        wide = bool(rng.integers(0, 4) == 0)
+        l_bias = int(rng.integers(0, 4))
+        seed = int(rng.integers(0, 1 << 30))
+        _say("random shape %d.%d: vocab=%d B=%d T=%d A=%d L=%d steps=%d corpus=%d wide=%d seed=%d"
+             % (block, case, vocab, B, T, A, L, steps, n_corpus, wide, seed))
+        corpus, prompts, acc, counts = _random_case(seed, vocab, n_corpus, B, T, A, L, steps)
+        use_corpus = corpus if rng.integers(0, 5) else None
+        sam.sam_set_layout_override(1 if wide else 0)
+        try:
+            g, status, _ = run_gpu(use_corpus, vocab, prompts, acc, counts, T, A, L, l_bias=l_bias,
+                                   collect_every=int(rng.integers(1, 4)))
+        finally:
+            sam.sam_set_layout_override(0)
+        r, _ = run_oracle(use_corpus, prompts, acc, counts, A, L, l_bias=l_bias,
+                          collect_every=1)
+        r = [x for x in r if x["step"] in {y["step"] for y in g}]
+        assert status == 0
+        assert_same(g, r, has_static=use_corpus is not None)
+
+
 def test_maximum_row_and_draft_sizes():
     """max_accept and draft_len at the largest values the library accepts."""
     B, T, A, L, steps, vocab = 3, 9000, 4096, 1024, 3, 3
