@@ -206,6 +206,23 @@ int sam_batch_step(sam_batch *batch, const int32_t *accepted, const int32_t *cou
                    int32_t *source, void *hip_stream);
 
 /*
+ * A recorded schedule of n_steps generation rounds in ONE launch, for offline
+ * replay and for measuring the path without launch gaps: every sequence runs
+ * through its own rows on its own, so none waits for another's longest row.
+ * The results are exactly those of n_steps calls of sam_batch_step.
+ *   accepted : device, int32 [n_steps, batch, max_accept].
+ *   counts   : device, int32 [n_steps, batch].
+ *   match_len, draft_len, source : device, int32 [n_steps, batch].
+ *   draft    : device, int32 [n_steps, batch, draft_len].
+ * Asynchronous.  Device-side faults as in sam_batch_step (a faulty row is
+ * skipped, the sequence goes on with its next row).
+ * Errors: SAM_EINVAL, SAM_EDEVICE.
+ */
+int sam_batch_replay(sam_batch *batch, int32_t n_steps, const int32_t *accepted,
+                     const int32_t *counts, int32_t *match_len, int32_t *draft,
+                     int32_t *draft_len, int32_t *source, void *hip_stream);
+
+/*
  * Tree draft from the static automaton (Section 3.2, Algorithm 4): for every
  * sequence, best-first expansion over the top-k successors starting at the static
  * cursor's state.  Entry 0 of a draft is the sequence's last token (parent -1,

@@ -27,6 +27,7 @@ EXPORTS = [
     "sam_batch_reset", "sam_set_progress_callback",
     "sam_batch_set_threshold", "sam_corpus_build_topk", "sam_corpus_export_topk",
     "sam_batch_tree_draft", "sam_corpus_save", "sam_corpus_load", "sam_corpus_load_host_only",
+    "sam_batch_replay",
 ]
 
 
@@ -68,6 +69,7 @@ def _load():
     L.sam_corpus_load_host_only.argtypes = [C.c_char_p, C.POINTER(vp)]
     L.sam_corpus_export_topk.argtypes = [vp, vp, vp, vp, vp]
     L.sam_batch_tree_draft.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+    L.sam_batch_replay.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
     L.sam_batch_reset.argtypes = [vp, vp, i32, vp, vp, vp]
     L.sam_batch_debug.argtypes = [vp, vp, vp, vp, vp, vp]
     L.sam_batch_sizes.argtypes = [vp, vp, vp, vp, vp]
@@ -266,6 +268,26 @@ def sam_batch_reset(batch: Batch, slots, prompt_tokens, prompt_offsets, stream=N
                                 _dev_ptr(prompt_tokens, torch.int32, "prompt_tokens"),
                                 _dev_ptr(prompt_offsets, torch.int64, "prompt_offsets"),
                                 _stream_ptr(stream)))
+
+
+def sam_batch_replay(batch: Batch, accepted, counts, match_len, draft, draft_len, source,
+                     stream=None) -> None:
+    """All rows of the [steps, ...] tensors in one launch."""
+    import torch
+    i32 = torch.int32
+    S = int(counts.shape[0])
+    B, A, L = batch.batch, batch.max_accept, batch.draft_len
+    for t, shp, name in ((accepted, (S, B, A), "accepted"), (counts, (S, B), "counts"),
+                         (match_len, (S, B), "match_len"), (draft, (S, B, L), "draft"),
+                         (draft_len, (S, B), "draft_len"), (source, (S, B), "source")):
+        if tuple(t.shape) != shp:
+            raise ValueError("%s must have shape %s" % (name, shp))
+    _check(_lib.sam_batch_replay(batch._h, S, _dev_ptr(accepted, i32, "accepted"),
+                                 _dev_ptr(counts, i32, "counts"),
+                                 _dev_ptr(match_len, i32, "match_len"),
+                                 _dev_ptr(draft, i32, "draft"),
+                                 _dev_ptr(draft_len, i32, "draft_len"),
+                                 _dev_ptr(source, i32, "source"), _stream_ptr(stream)))
 
 
 def sam_batch_set_threshold(batch: Batch, l_threshold: int) -> None:

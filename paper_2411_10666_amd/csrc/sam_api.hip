@@ -416,6 +416,21 @@ int sam_batch_step(sam_batch *bt, const int32_t *accepted, const int32_t *counts
     return SAM_OK;
 }
 
+int sam_batch_replay(sam_batch *bt, int32_t n_steps, const int32_t *accepted, const int32_t *counts,
+                     int32_t *match_len, int32_t *draft, int32_t *draft_len, int32_t *source,
+                     void *hip_stream)
+{
+    if (!bt) return fail(SAM_EINVAL, "sam_batch_replay: batch is NULL");
+    if (!accepted || !counts || !match_len || !draft || !draft_len || !source)
+        return fail(SAM_EINVAL, "sam_batch_replay: NULL buffer");
+    if (n_steps < 1) return fail(SAM_EINVAL, "sam_batch_replay: n_steps must be >= 1");
+    StaticView S = bt->corpus ? bt->corpus->view : StaticView{};
+    hipError_t e = launch_replay(S, bt->view, n_steps, accepted, counts, match_len, draft,
+                                 draft_len, source, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail_hip("sam_batch_replay: launch", e);
+    return SAM_OK;
+}
+
 int sam_batch_tree_draft(sam_batch *bt, int32_t max_size, int32_t *tokens, int32_t *parents,
                          float *probs, int32_t *sizes, void *hip_stream)
 {

@@ -51,6 +51,10 @@ hipError_t launch_feed(const StaticView &S, const BatchView &B, const int32_t *s
                        int n_seqs, const int32_t *tokens, const int64_t *offsets,
                        const int32_t *counts, int32_t *match_len, int32_t *draft,
                        int32_t *draft_len, int32_t *source, hipStream_t stream);
+// A whole schedule of n_steps steps in one launch (rows [step, sequence] of every array).
+hipError_t launch_replay(const StaticView &S, const BatchView &B, int n_steps,
+                         const int32_t *accepted, const int32_t *counts, int32_t *match_len,
+                         int32_t *draft, int32_t *draft_len, int32_t *source, hipStream_t stream);
 // seq_map NULL: fresh records and cursors for sequences 0 .. n_seqs-1 (slot tables
 // are cleared by the caller).  Otherwise: the listed sequences, slot tables included.
 hipError_t launch_reset(const BatchView &B, const int32_t *seq_map, int n_seqs,

@@ -509,6 +509,120 @@ __device__ __forceinline__ void flush_last(const DynSeq &D, const DynCursor<L> &
     if (lane == 0) L::store_rec(D.rec, c.last, LR);
 }
 
+// ---- per-wave work shared by the step, ingest and replay kernels -------------
+
+// Wave 0: feed `count` tokens to the static cursor; stops in front of a token
+// outside the vocabulary (wave 1 reports it).
+__device__ __forceinline__ void static_feed(const StaticView &S, const int32_t *tok, int64_t count,
+                                            uint32_t vocab, int lane, uint32_t &s, uint32_t &l,
+                                            uint32_t &e, uint32_t &fault)
+{
+    bool stop = false;
+    for (int64_t base = 0; base < count && !stop; base += 64) {
+        const int m = (int)((count - base) < 64 ? (count - base) : 64);
+        uint32_t tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
+        pin_v(tv);
+        for (int i = 0; i < m; i++) {
+            const uint32_t t = lane_get(tv, i);
+            if (t >= vocab) { stop = true; break; }
+            static_transfer(S, t, lane, s, l, e, fault);
+        }
+    }
+}
+
+// Wave 1: append `count` tokens to the sequence's dynamic automaton and text.
+template <class L>
+__device__ __forceinline__ void dyn_feed(const DynSeq &D, const int32_t *tok, int64_t count,
+                                         uint32_t vocab, int lane, DynCursor<L> &c,
+                                         uint32_t &fault)
+{
+    bool stop = false;
+    for (int64_t base = 0; base < count && !stop; base += 64) {
+        const int m = (int)((count - base) < 64 ? (count - base) : 64);
+        uint32_t tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
+        pin_v(tv);
+        c.pf_ok = false;
+        const uint32_t n_chunk = c.n;
+        int fed = 0;
+        for (; fed < m; fed++) {
+            const uint32_t t = lane_get(tv, fed);
+            if (t >= vocab) { stop = true; fault |= SAM_STATUS_TOKEN_BIT; break; }
+            uint32_t tn = kNil;
+            if (fed + 1 < m) {
+                tn = lane_get(tv, fed + 1);
+                if (tn >= vocab) tn = kNil;
+            }
+            dyn_expand<L>(D, t, tn, lane, c, fault);
+        }
+        // the sequence's text, one coalesced store per chunk
+        if (lane < fed) D.text[n_chunk + lane] = (int32_t)tv;
+    }
+}
+
+template <class L>
+__device__ __forceinline__ DynSeq dyn_region(const BatchView &B, int b)
+{
+    DynSeq D;
+    D.text = B.dyn_text + (size_t)b * B.max_seq_len;
+    D.rec = reinterpret_cast<char *>(B.dyn_rec) +
+            (size_t)b * B.max_states * (B.compact ? sizeof(DynRecCompact) : sizeof(DynRec));
+    D.slots = reinterpret_cast<char *>(B.dyn_slots) + (size_t)b * B.dyn_buckets * 128;
+    D.n_buckets = B.dyn_buckets;
+    return D;
+}
+
+template <class L>
+__device__ __forceinline__ void load_cursor(const SeqMeta *meta, DynCursor<L> &c)
+{
+    c.n = uni(meta->n); c.n_states = uni(meta->n_states); c.last = uni(meta->last);
+    c.n_trans = uni(meta->n_trans);
+    c.P = uni(meta->s2);
+    c.RP.len = uni(meta->p_len); c.RP.link = uni(meta->p_link);
+    c.RP.endpos = uni(meta->p_endpos); c.RP.head = uni(meta->p_head);
+    c.RP.itok = uni(meta->p_itok); c.RP.idst = uni(meta->p_idst);
+    c.pf_ok = false;
+    c.pf.b = 0; c.pf.mh = 0; c.pf.me = 0;
+    c.pf.sl = typename L::RawSlot();
+}
+
+// all of the dynamic cursor except meta->n (see the kernels for why)
+template <class L>
+__device__ __forceinline__ void store_cursor(SeqMeta *meta, const DynCursor<L> &c)
+{
+    meta->n_states = c.n_states; meta->last = c.last; meta->n_trans = c.n_trans;
+    meta->s2 = c.P;
+    meta->p_len = c.RP.len; meta->p_link = c.RP.link; meta->p_endpos = c.RP.endpos;
+    meta->p_head = c.RP.head; meta->p_itok = c.RP.itok; meta->p_idst = c.RP.idst;
+}
+
+// Wave 0 after the barrier: choose the source (Section 3.2) and gather the draft.
+__device__ __forceinline__ void emit_draft(const StaticView &S, const BatchView &B, int b, int lane,
+                                           uint32_t l1, uint32_t e1, uint32_t l2, uint32_t e2,
+                                           uint32_t n1, int32_t *match_len, int32_t *draft,
+                                           int32_t *draft_len, int32_t *source)
+{
+    const bool use_static = B.has_static && ((int64_t)l1 > (int64_t)l2 + (int64_t)B.l_bias);
+    const uint32_t ml = use_static ? l1 : l2;
+    const uint32_t p = use_static ? e1 : e2;
+    const int32_t *T = use_static ? S.text : B.dyn_text + (size_t)b * B.max_seq_len;
+    const uint32_t Tn = use_static ? S.n_tokens : n1;
+    const int Ld = B.draft_len;
+    int dl = 0;
+    if (ml > 0) {
+        const uint32_t room = Tn - p;
+        dl = room < (uint32_t)Ld ? (int)room : Ld;
+    }
+    for (int i = lane; i < Ld; i += 64)
+        draft[(size_t)b * Ld + i] = i < dl ? T[p + i] : -1;
+    if (lane == 0) {
+        match_len[b] = (int32_t)ml;
+        draft_len[b] = dl;
+        int src = ml == 0 ? 0 : (use_static ? 2 : 1);
+        if (B.l_threshold >= 0 && (int64_t)ml <= (int64_t)B.l_threshold) src = 3;
+        source[b] = src;
+    }
+}
+
 }  // namespace
 
 // One workgroup (2 waves) per sequence.  kIngest: sequence b is fed
@@ -554,67 +668,19 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
 
     if (wave == 0) {
         uint32_t s = uni(meta->s1), l = uni(meta->l1), e = uni(meta->e1);
-        if (B.has_static) {
-            bool stop = false;
-            for (int64_t base = 0; base < count && !stop; base += 64) {
-                const int m = (int)((count - base) < 64 ? (count - base) : 64);
-                uint32_t tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
-                pin_v(tv);
-                for (int i = 0; i < m; i++) {
-                    const uint32_t t = lane_get(tv, i);
-                    if (t >= vocab) { stop = true; break; }
-                    static_transfer(S, t, lane, s, l, e, fault);
-                }
-            }
-        }
+        if (B.has_static) static_feed(S, tok, count, vocab, lane, s, l, e, fault);
         if (lane == 0) { sh[0] = s; sh[1] = l; sh[2] = e; sh[6] = fault & SAM_STATUS_INTERNAL_BIT; }
     } else {
-        DynSeq D;
-        D.text = B.dyn_text + (size_t)b * B.max_seq_len;
-        D.rec = reinterpret_cast<char *>(B.dyn_rec) +
-                (size_t)b * B.max_states * (B.compact ? sizeof(DynRecCompact) : sizeof(DynRec));
-        D.slots = reinterpret_cast<char *>(B.dyn_slots) + (size_t)b * B.dyn_buckets * 128;
-        D.n_buckets = B.dyn_buckets;
+        const DynSeq D = dyn_region<L>(B, b);
         DynCursor<L> c;
-        c.n = n0; c.n_states = uni(meta->n_states); c.last = uni(meta->last);
-        c.n_trans = uni(meta->n_trans);
-        c.P = uni(meta->s2);
-        c.RP.len = uni(meta->p_len); c.RP.link = uni(meta->p_link);
-        c.RP.endpos = uni(meta->p_endpos); c.RP.head = uni(meta->p_head);
-        c.RP.itok = uni(meta->p_itok); c.RP.idst = uni(meta->p_idst);
-        c.pf_ok = false;
-        c.pf.b = 0; c.pf.mh = 0; c.pf.me = 0;
-        c.pf.sl = typename L::RawSlot();
-        bool stop = false;
-        for (int64_t base = 0; base < count && !stop; base += 64) {
-            const int m = (int)((count - base) < 64 ? (count - base) : 64);
-            uint32_t tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
-            pin_v(tv);
-            c.pf_ok = false;
-            const uint32_t n_chunk = c.n;
-            int fed = 0;
-            for (; fed < m; fed++) {
-                const uint32_t t = lane_get(tv, fed);
-                if (t >= vocab) { stop = true; fault |= SAM_STATUS_TOKEN_BIT; break; }
-                uint32_t tn = kNil;
-                if (fed + 1 < m) {
-                    tn = lane_get(tv, fed + 1);
-                    if (tn >= vocab) tn = kNil;
-                }
-                dyn_expand<L>(D, t, tn, lane, c, fault);
-            }
-            // the sequence's text, one coalesced store per chunk
-            if (lane < fed) D.text[n_chunk + lane] = (int32_t)tv;
-        }
+        load_cursor<L>(meta, c);
+        dyn_feed<L>(D, tok, count, vocab, lane, c, fault);
         if (c.n != n0) flush_last<L>(D, c, lane);
         if (lane == 0) {
             sh[3] = c.P == kNil ? 0u : c.RP.len;
             sh[4] = c.P == kNil ? 0u : c.RP.endpos;
             sh[5] = c.n;
-            meta->n_states = c.n_states; meta->last = c.last; meta->n_trans = c.n_trans;
-            meta->s2 = c.P;
-            meta->p_len = c.RP.len; meta->p_link = c.RP.link; meta->p_endpos = c.RP.endpos;
-            meta->p_head = c.RP.head; meta->p_itok = c.RP.itok; meta->p_idst = c.RP.idst;
+            store_cursor<L>(meta, c);
             if (fault) {
                 meta->status |= fault;
                 atomicOr(B.status, fault);
@@ -628,32 +694,85 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
         return;
     }
     const uint32_t s1 = sh[0], l1 = sh[1], e1 = sh[2];
-    const uint32_t l2 = sh[3], e2 = sh[4], n1 = sh[5];
     if (lane == 0) {
         meta->s1 = s1; meta->l1 = l1; meta->e1 = e1;
         if (sh[6]) atomicOr(B.status, sh[6]);
     }
     if (kIngest) return;
+    emit_draft(S, B, b, lane, l1, e1, sh[3], sh[4], sh[5], match_len, draft, draft_len, source);
+}
 
-    const bool use_static = B.has_static && ((int64_t)l1 > (int64_t)l2 + (int64_t)B.l_bias);
-    const uint32_t ml = use_static ? l1 : l2;
-    const uint32_t p = use_static ? e1 : e2;
-    const int32_t *T = use_static ? S.text : B.dyn_text + (size_t)b * B.max_seq_len;
-    const uint32_t Tn = use_static ? S.n_tokens : n1;
-    const int Ld = B.draft_len;
-    int dl = 0;
-    if (ml > 0) {
-        const uint32_t room = Tn - p;
-        dl = room < (uint32_t)Ld ? (int)room : Ld;
+// The same work for a whole schedule of steps in one launch: workgroup b runs
+// sequence b through steps 0 .. n_steps-1 on its own, so no sequence waits for
+// the longest row of another and nothing is launched in between.  Step s reads
+// accepted[s, b, :] and counts[s, b] and writes row (s, b) of the outputs.  The
+// cursors stay in registers from step to step.
+template <class L>
+__global__ __launch_bounds__(128) void sam_replay_kernel(StaticView S, BatchView B, int n_steps,
+                                                          const int32_t *__restrict__ accepted,
+                                                          const int32_t *__restrict__ counts,
+                                                          int32_t *__restrict__ match_len,
+                                                          int32_t *__restrict__ draft,
+                                                          int32_t *__restrict__ draft_len,
+                                                          int32_t *__restrict__ source)
+{
+    __shared__ uint32_t sh[8];
+    const int b = blockIdx.x;
+    const int wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    SeqMeta *meta = &B.meta[b];
+    const uint32_t vocab = (uint32_t)B.vocab;
+    const size_t nb = (size_t)B.batch;
+    uint32_t fault = 0;
+    uint32_t n_cur = uni(meta->n);
+
+    uint32_t s = 0, l = 0, e = 0;
+    DynSeq D = dyn_region<L>(B, b);
+    DynCursor<L> c;
+    if (wave == 0) { s = uni(meta->s1); l = uni(meta->l1); e = uni(meta->e1); }
+    load_cursor<L>(meta, c);
+    const uint32_t n_first = n_cur;
+
+    for (int step = 0; step < n_steps; step++) {
+        const int32_t *tok = accepted + ((size_t)step * nb + b) * B.max_accept;
+        int64_t count = counts[(size_t)step * nb + b];
+        if (count < 0 || count > B.max_accept) { fault |= SAM_STATUS_COUNT_BIT; count = 0; }
+        count = (int64_t)uni((uint32_t)count);
+        if ((int64_t)n_cur + count > (int64_t)B.max_seq_len) { fault |= SAM_STATUS_CAPACITY_BIT; count = 0; }
+        if (wave == 0) {
+            if (B.has_static) static_feed(S, tok, count, vocab, lane, s, l, e, fault);
+        } else {
+            dyn_feed<L>(D, tok, count, vocab, lane, c, fault);
+            if (lane == 0) {
+                sh[3] = c.P == kNil ? 0u : c.RP.len;
+                sh[4] = c.P == kNil ? 0u : c.RP.endpos;
+                sh[5] = c.n;
+            }
+        }
+        __syncthreads();                 // the step's text and wave 1's cursor are visible
+        n_cur = sh[5];
+        if (wave == 0)
+            emit_draft(S, B, b, lane, l, e, sh[3], sh[4], n_cur, match_len + (size_t)step * nb,
+                       draft + (size_t)step * nb * B.draft_len, draft_len + (size_t)step * nb,
+                       source + (size_t)step * nb);
+        __syncthreads();                 // sh is rewritten by the next step
     }
-    for (int i = lane; i < Ld; i += 64)
-        draft[(size_t)b * Ld + i] = i < dl ? T[p + i] : -1;
-    if (lane == 0) {
-        match_len[b] = (int32_t)ml;
-        draft_len[b] = dl;
-        int src = ml == 0 ? 0 : (use_static ? 2 : 1);
-        if (B.l_threshold >= 0 && (int64_t)ml <= (int64_t)B.l_threshold) src = 3;
-        source[b] = src;
+
+    if (wave == 0) {
+        if (lane == 0) {
+            meta->s1 = s; meta->l1 = l; meta->e1 = e;
+            if (fault & SAM_STATUS_INTERNAL_BIT) atomicOr(B.status, SAM_STATUS_INTERNAL_BIT);
+        }
+    } else {
+        if (c.n != n_first) flush_last<L>(D, c, lane);
+        if (lane == 0) {
+            store_cursor<L>(meta, c);
+            meta->n = c.n;
+            if (fault) {
+                meta->status |= fault;
+                atomicOr(B.status, fault);
+            }
+        }
     }
 }
 
@@ -737,6 +856,20 @@ hipError_t launch_feed(const StaticView &S, const BatchView &B, const int32_t *s
                                seq_map, tokens, offsets, counts, match_len, draft, draft_len,
                                source);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_replay(const StaticView &S, const BatchView &B, int n_steps,
+                         const int32_t *accepted, const int32_t *counts, int32_t *match_len,
+                         int32_t *draft, int32_t *draft_len, int32_t *source, hipStream_t stream)
+{
+    const dim3 grid(B.batch), block(128);
+    if (B.compact)
+        hipLaunchKernelGGL((sam_replay_kernel<CompactDyn>), grid, block, 0, stream, S, B, n_steps,
+                           accepted, counts, match_len, draft, draft_len, source);
+    else
+        hipLaunchKernelGGL((sam_replay_kernel<WideDyn>), grid, block, 0, stream, S, B, n_steps,
+                           accepted, counts, match_len, draft, draft_len, source);
     return hipGetLastError();
 }
 

@@ -370,6 +370,64 @@ def test_loaded_corpus_behaves_like_a_built_one(tmp_path):
     assert_same(g, r)
 
 
+@pytest.mark.parametrize("seed,vocab,with_corpus", [(80, 2, True), (81, 3, True), (82, 5, False),
+                                                    (83, 32000, True)])
+def test_replay_equals_stepwise(seed, vocab, with_corpus):
+    """The single-launch replay of a schedule gives the outputs of the step calls,
+    including rows with faults, and can be continued by ordinary steps."""
+    import torch
+    from paper_2411_10666_amd import binding as sam
+    dev = torch.device("cuda:0")
+    B, T, A, L, steps = 12, 260, 7, 10, 30
+    _say("replay seed=%d vocab=%d corpus=%s" % (seed, vocab, with_corpus))
+    corpus, prompts, acc, counts = _random_case(seed, vocab, 2500, B, T, A, L, steps)
+    if not with_corpus:
+        corpus = None
+    acc_g, cnt_g = acc.copy(), counts.copy()
+    cnt_r = counts.copy()
+    cnt_g[5, 2] = A + 3; cnt_r[5, 2] = 0                  # a bad count: row skipped
+    if counts[7, 4] >= 2:
+        acc_g[7, 4, 1] = vocab + 9; cnt_r[7, 4] = 1        # a bad token: row cut there
+    r, _ = run_oracle(corpus, prompts, acc, cnt_r, A, L)
+    gc = sam.sam_build(corpus, vocab) if corpus is not None else None
+    offs = np.zeros(B + 1, np.int64); offs[1:] = np.cumsum([len(p) for p in prompts])
+    flat = np.concatenate(prompts) if offs[-1] else np.zeros(1, np.int32)
+    batch = sam.sam_batch_init(gc, torch.from_numpy(flat).to(dev), torch.from_numpy(offs).to(dev),
+                               B, vocab, T, A, L)
+    i32 = dict(dtype=torch.int32, device=dev)
+    first = 20                                            # replay 20 rows, then step the rest
+    ml = torch.zeros(first, B, **i32); dl = torch.zeros(first, B, **i32)
+    src = torch.zeros(first, B, **i32); dr = torch.zeros(first, B, L, **i32)
+    sam.sam_batch_replay(batch, torch.from_numpy(acc_g[:first]).to(dev),
+                         torch.from_numpy(cnt_g[:first]).to(dev), ml, dr, dl, src)
+    torch.cuda.synchronize()
+    for s_ in range(first):
+        assert np.array_equal(ml[s_].cpu().numpy(), r[s_]["match_len"]), s_
+        assert np.array_equal(src[s_].cpu().numpy(), r[s_]["source"]), s_
+        assert np.array_equal(dl[s_].cpu().numpy(), r[s_]["draft_len"]), s_
+        assert np.array_equal(dr[s_].cpu().numpy(), r[s_]["draft"]), s_
+    m1 = torch.empty(B, **i32); d1 = torch.empty(B, **i32); s1 = torch.empty(B, **i32)
+    r1 = torch.empty(B, L, **i32)
+    cur = [torch.empty(B, **i32) for _ in range(4)]
+    siz = [torch.empty(B, **i32) for _ in range(3)]
+    for s_ in range(first, steps):
+        sam.sam_batch_step(batch, torch.from_numpy(acc_g[s_]).to(dev),
+                           torch.from_numpy(cnt_g[s_]).to(dev), m1, r1, d1, s1)
+        sam.sam_batch_debug(batch, *cur)
+        sam.sam_batch_sizes(batch, *siz)
+        torch.cuda.synchronize()
+        assert np.array_equal(m1.cpu().numpy(), r[s_]["match_len"]), s_
+        assert np.array_equal(r1.cpu().numpy(), r[s_]["draft"]), s_
+        gcur = np.stack([c.cpu().numpy() for c in cur], axis=1)
+        rcur = r[s_]["cursors"]
+        if corpus is None:
+            gcur, rcur = gcur[:, 2:], rcur[:, 2:]
+        assert np.array_equal(gcur, rcur), s_
+        assert np.array_equal(np.stack([c.cpu().numpy() for c in siz], axis=1), r[s_]["sizes"]), s_
+    want = sam.SAM_STATUS_COUNT | (sam.SAM_STATUS_TOKEN if counts[7, 4] >= 2 else 0)
+    assert sam.sam_batch_status(batch) == want
+
+
 def test_reset_recycles_sequences():
     """Continuous batching: some sequences are replaced by new requests in the
     middle of a run; the others carry on untouched."""
