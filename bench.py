@@ -30,6 +30,7 @@ if ROOT not in sys.path:
 from paper_2411_10666_amd.synth import CONFIGS, make_workload  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0
+HOST_THREADS = 16          # upper limit of worker threads of the CPU leg
 
 # Algorithmic bytes one match-step moves, per workload: the operation counts of
 # the method (probes, suffix-link reads, inserts, redirects, clone copies, state
@@ -247,10 +248,51 @@ def cpu_leg(w):
         ob.step(acc[s], cnt[s])
     dt = time.perf_counter() - t0
     ms = int(cnt.sum())
-    return dict(value=ms / dt, unit="match-steps/s", cores=1, kind="oracle",
-                sample="%d of %d sequences, whole %d-step schedule (%d match-steps); "
-                       "corpus build (%.1f s) and prompt ingest not timed%s"
-                       % (nb, spec.batch, w.steps, ms, build_s, note))
+    out = dict(value=ms / dt, unit="match-steps/s", cores=1, kind="oracle",
+               sample="%d of %d sequences, whole %d-step schedule (%d match-steps); "
+                      "corpus build (%.1f s) and prompt ingest not timed%s"
+                      % (nb, spec.batch, w.steps, ms, build_s, note))
+    # The same work once more with the sequences dealt out to one thread per host
+    # core (the checker itself is unchanged: its calls release the interpreter lock
+    # and share the read-only corpus automaton).
+    threads = max(1, min(nb, HOST_THREADS, os.cpu_count() or 1))
+    if threads > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        del ob
+        groups = [list(range(t, nb, threads)) for t in range(threads)]
+        parts = [(Batch(static, corpus, [w.prompts[b] for b in g], spec.max_accept,
+                        spec.draft_len, spec.l_bias),
+                  np.ascontiguousarray(acc[:, g]), np.ascontiguousarray(cnt[:, g]))
+                 for g in groups]
+
+        def work(part):
+            b, a, c = part
+            b.run(a, c)       # the same steps, looped inside one foreign call
+
+        with ThreadPoolExecutor(threads) as pool:
+            t0 = time.perf_counter()
+            list(pool.map(work, parts))
+            dt = time.perf_counter() - t0
+        out["all_cores"] = dict(value=ms / dt, unit="match-steps/s", cores=threads)
+    return out
+
+
+def memory_leg(table_bytes):
+    """What the device's memory system gives for the path's access patterns."""
+    from paper_2411_10666_amd import binding as sam
+    chase = {name: sam.sam_membench(sam.MEMBENCH_CHASE, size, hops)
+             for name, size, hops in (("l2_1MiB", 1 << 20, 20000), ("mall_64MiB", 64 << 20, 20000),
+                                      ("hbm_4GiB", 4 << 30, 20000))}
+    table = 4096
+    while table < max(table_bytes, 1 << 30):
+        table *= 2
+    return {
+        "dependent_line_load_ns": chase,
+        "random_16B_reads_per_s": sam.sam_membench(sam.MEMBENCH_GATHER, table, 256, 16384),
+        "random_read_table_bytes": table,
+        "copy_bytes_per_s": sam.sam_membench(sam.MEMBENCH_COPY, 1 << 30),
+        "empty_launch_us": sam.sam_membench(sam.MEMBENCH_LAUNCH, 0, 2000, 64),
+    }
 
 
 def main():
@@ -260,6 +302,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", default="cfg2", choices=sorted(CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-memory-system", action="store_true",
+                    help="skip the memory-system measurements (memory_system, latency_bound)")
     ap.add_argument("--tree-draft", default="",
                     help="K,MAX_SIZE: also time sam_batch_tree_draft (reported as tree_draft)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -342,6 +386,21 @@ def main():
             "avg_launch_ms": per_step_ms,
         },
     }
+    if not args.no_memory_system:
+        m = memory_leg(g["static_bytes"])
+        out["memory_system"] = m
+        # Little's law: each walking wavefront has one dependent line load in flight
+        # (two wavefronts per sequence, one when there is no corpus automaton).
+        chains = spec.batch * (2 if w.corpus is not None else 1)
+        traffic = out["roofline"]["traffic"]
+        out["latency_bound"] = {
+            "chains_in_flight": chains,
+            "line_loads_per_s_all_hbm": chains / (m["dependent_line_load_ns"]["hbm_4GiB"] * 1e-9),
+            "line_loads_per_s_all_l2": chains / (m["dependent_line_load_ns"]["l2_1MiB"] * 1e-9),
+            "measured_hbm_line_fetches_per_s":
+                None if traffic is None else traffic / 128.0 / (per_step_ms * 1e-3),
+            "random_read_peak_frac": (achieved * 1e9 / 16.0) / m["random_16B_reads_per_s"],
+        }
     if g["replay"]:
         out["single_launch_replay"] = g["replay"]
     if g["tree"]:

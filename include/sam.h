@@ -301,6 +301,32 @@ int sam_batch_info(const sam_batch *batch, int64_t *device_bytes);
 
 void sam_batch_free(sam_batch *batch);
 
+/*
+ * Measurement aid, not part of the method: what the memory system of the
+ * current device delivers for the access patterns of the path, so that the
+ * path's own throughput can be put beside it.  Allocates its own device
+ * memory, runs on the default stream, returns when done.
+ *   SAM_MEMBENCH_CHASE  : one wavefront follows `count` dependent loads, each of
+ *                         a whole 128-byte line (the shape of a bucket probe),
+ *                         through a pseudo-random cycle over `size` bytes
+ *                         (a power of two); footprints up to 128 MiB are walked
+ *                         once beforehand, larger ones start cold.
+ *                         result = nanoseconds per load.
+ *   SAM_MEMBENCH_GATHER : `workgroups` x 256 lanes, each `count` independent
+ *                         random 16-byte reads from a table of `size` bytes.
+ *                         result = reads per second.
+ *   SAM_MEMBENCH_COPY   : device copy of `size` bytes.
+ *                         result = bytes per second, read + written.
+ *   SAM_MEMBENCH_LAUNCH : `count` back-to-back launches of an empty kernel of
+ *                         `workgroups` x 128 lanes.  result = microseconds each.
+ * Errors: SAM_EINVAL (sizes out of range), SAM_EDEVICE.
+ */
+#define SAM_MEMBENCH_CHASE  0
+#define SAM_MEMBENCH_GATHER 1
+#define SAM_MEMBENCH_COPY   2
+#define SAM_MEMBENCH_LAUNCH 3
+int sam_membench(int32_t kind, int64_t size, int64_t count, int32_t workgroups, double *result);
+
 #ifdef __cplusplus
 }
 #endif

@@ -600,3 +600,19 @@ int obatch_step(oseq **seqs, int32_t B, const int32_t *accepted, const int32_t *
     }
     return 0;
 }
+
+/* n_steps batch steps in a row: row i of accepted [n_steps, B, A] and counts
+ * [n_steps, B] gives row i of match_len/source/draft_len [n_steps, B] and draft
+ * [n_steps, B, L].  Nothing but the loop over obatch_step. */
+int obatch_run(oseq **seqs, int32_t B, int32_t n_steps, const int32_t *accepted,
+               const int32_t *counts, int32_t A, int32_t L, int32_t l_bias, int32_t l_threshold,
+               int32_t *match_len, int32_t *source, int32_t *draft_len, int32_t *draft)
+{
+    for (int32_t i = 0; i < n_steps; i++) {
+        const size_t r = (size_t)i * B;
+        if (obatch_step(seqs, B, accepted + r * A, counts + r, A, L, l_bias, l_threshold,
+                        match_len + r, source + r, draft_len + r, draft + r * L) != 0)
+            return -1;
+    }
+    return 0;
+}

@@ -89,6 +89,10 @@ def lib():
                                       C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                       _i32p, _i32p, _i32p, _i32p]
             L.obatch_step.restype = C.c_int
+            L.obatch_run.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_int32, _i32p, _i32p,
+                                     C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                     _i32p, _i32p, _i32p, _i32p]
+            L.obatch_run.restype = C.c_int
             _lib = L
     return _lib
 
@@ -278,6 +282,25 @@ class Batch:
                                  _p32(d))
         if rc != 0:
             raise MemoryError("obatch_step failed")
+        return ml, src, dl, d
+
+    def run(self, accepted, counts):
+        """All rows of accepted [S, B, A] and counts [S, B] one after the other in
+        one call; returns (match_len, source, draft_len, draft) with a leading S."""
+        B = len(self.seqs)
+        cnt = np.ascontiguousarray(counts, dtype=np.int32)
+        S = cnt.shape[0]
+        cnt = cnt.reshape(S, B)
+        acc = np.ascontiguousarray(accepted, dtype=np.int32).reshape(S, B, self.A)
+        ml = np.empty((S, B), dtype=np.int32)
+        src = np.empty((S, B), dtype=np.int32)
+        dl = np.empty((S, B), dtype=np.int32)
+        d = np.empty((S, B, self.Ld), dtype=np.int32)
+        rc = self._L.obatch_run(self._arr, B, S, _p32(acc), _p32(cnt), self.A, self.Ld,
+                                self.l_bias, self.l_threshold, _p32(ml), _p32(src), _p32(dl),
+                                _p32(d))
+        if rc != 0:
+            raise MemoryError("obatch_run failed")
         return ml, src, dl, d
 
     def cursors(self):

@@ -27,7 +27,7 @@ EXPORTS = [
     "sam_batch_reset", "sam_set_progress_callback",
     "sam_batch_set_threshold", "sam_corpus_build_topk", "sam_corpus_export_topk",
     "sam_batch_tree_draft", "sam_corpus_save", "sam_corpus_load", "sam_corpus_load_host_only",
-    "sam_batch_replay",
+    "sam_batch_replay", "sam_membench",
 ]
 
 
@@ -288,6 +288,17 @@ def sam_batch_replay(batch: Batch, accepted, counts, match_len, draft, draft_len
                                  _dev_ptr(draft, i32, "draft"),
                                  _dev_ptr(draft_len, i32, "draft_len"),
                                  _dev_ptr(source, i32, "source"), _stream_ptr(stream)))
+
+
+MEMBENCH_CHASE, MEMBENCH_GATHER, MEMBENCH_COPY, MEMBENCH_LAUNCH = 0, 1, 2, 3
+
+
+def sam_membench(kind: int, size: int = 0, count: int = 1, workgroups: int = 1) -> float:
+    """Memory-system measurement of the current device (see include/sam.h)."""
+    out = C.c_double(0.0)
+    _check(_lib.sam_membench(C.c_int32(kind), C.c_int64(size), C.c_int64(count),
+                             C.c_int32(workgroups), C.byref(out)))
+    return out.value
 
 
 def sam_batch_set_threshold(batch: Batch, l_threshold: int) -> None:

@@ -7,8 +7,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsam_hip.so")
-SOURCES = ["sam_api.hip", "sam_kernels.hip", "sam_tree.hip", "sam_host.cpp"]
-HEADERS = ["sam_layout.h", "sam_device.h", "sam_host.h", os.path.join("..", "..", "include", "sam.h")]
+SOURCES = ["sam_api.hip", "sam_kernels.hip", "sam_tree.hip", "sam_membench.hip", "sam_host.cpp"]
+HEADERS = ["sam_layout.h", "sam_device.h", "sam_host.h", "sam_membench.h", os.path.join("..", "..", "include", "sam.h")]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",

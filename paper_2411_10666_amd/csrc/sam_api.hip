@@ -13,6 +13,7 @@
 #include "../../include/sam.h"
 #include "sam_device.h"
 #include "sam_host.h"
+#include "sam_membench.h"
 
 using namespace sam;
 
@@ -429,6 +430,14 @@ int sam_batch_replay(sam_batch *bt, int32_t n_steps, const int32_t *accepted, co
                                  draft_len, source, (hipStream_t)hip_stream);
     if (e != hipSuccess) return fail_hip("sam_batch_replay: launch", e);
     return SAM_OK;
+}
+
+int sam_membench(int32_t kind, int64_t size, int64_t count, int32_t workgroups, double *result)
+{
+    if (!result) return fail(SAM_EINVAL, "sam_membench: result is NULL");
+    std::string err;
+    const int rc = membench(kind, size, count, workgroups, result, err);
+    return rc == SAM_OK ? SAM_OK : fail(rc, err);
 }
 
 int sam_batch_tree_draft(sam_batch *bt, int32_t max_size, int32_t *tokens, int32_t *parents,

@@ -291,6 +291,21 @@ def test_batch_matches_single_sequences():
             assert (d[b] == r["draft"]).all()
 
 
+def test_batch_run_is_the_loop_over_steps():
+    rng = np.random.default_rng(19)
+    corpus = np.array(_rand_text(rng, 300, 5), dtype=np.int32)
+    st = Sam.build(corpus)
+    B, A, L, S = 4, 5, 7, 12
+    prompts = [np.array(_rand_text(rng, 15, 5), dtype=np.int32) for _ in range(B)]
+    counts = rng.integers(0, A + 1, size=(S, B)).astype(np.int32)
+    acc = rng.integers(0, 5, size=(S, B, A)).astype(np.int32)
+    whole = Batch(st, corpus, prompts, A, L, 0).run(acc, counts)
+    stepped = Batch(st, corpus, prompts, A, L, 0)
+    for i in range(S):
+        for got, want in zip(stepped.step(acc[i], counts[i]), whole):
+            assert (got == want[i]).all()
+
+
 # --------------------------------------------------------------------------
 # tree drafts: Algorithm 3 (freq, top-k, probabilities) and Algorithm 4 (Prim)
 

@@ -524,3 +524,23 @@ def test_init_errors():
     with pytest.raises(sam.SamError) as e:
         sam.sam_batch_init(host_only, tok, off, 1, 5, 16, 4, 4)
     assert e.value.code == sam.SAM_EINVAL
+
+
+def test_membench_gives_plausible_figures():
+    """The measurement aid runs and its figures have the right order of magnitude
+    (wide brackets: this is no performance test)."""
+    from paper_2411_10666_amd import binding as sam
+    l2 = sam.sam_membench(sam.MEMBENCH_CHASE, 1 << 20, 4000)
+    far = sam.sam_membench(sam.MEMBENCH_CHASE, 1 << 30, 4000)
+    assert 20.0 < l2 < 2000.0 and l2 < far < 5000.0
+    reads = sam.sam_membench(sam.MEMBENCH_GATHER, 256 << 20, 64, 4096)
+    assert 1e9 < reads < 1e12
+    copy = sam.sam_membench(sam.MEMBENCH_COPY, 256 << 20)
+    assert 2e11 < copy < 8.5e12
+    launch = sam.sam_membench(sam.MEMBENCH_LAUNCH, 0, 500, 64)
+    assert 0.2 < launch < 200.0
+    for args in ((sam.MEMBENCH_CHASE, 3 << 20, 10), (sam.MEMBENCH_GATHER, 1 << 20, 0, 1),
+                 (sam.MEMBENCH_COPY, 16), (7, 1 << 20, 1)):
+        with pytest.raises(sam.SamError) as e:
+            sam.sam_membench(*args)
+        assert e.value.code == sam.SAM_EINVAL
