@@ -89,7 +89,18 @@ def gpu_leg(w, steps, warmup, tree=None, replay=True):
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     t0 = time.time()
-    corpus = sam.sam_build(w.corpus, spec.vocab) if w.corpus is not None else None
+    said = [t0]
+
+    def progress(phase, done, total):       # a line now and then during long builds
+        if time.time() - said[0] > 20.0:
+            said[0] = time.time()
+            _log("corpus build, %s: %d of %d" % (phase, done, total))
+
+    sam.sam_set_progress_callback(progress)
+    try:
+        corpus = sam.sam_build(w.corpus, spec.vocab) if w.corpus is not None else None
+    finally:
+        sam.sam_set_progress_callback(None)
     build_s = time.time() - t0
     info = sam.sam_corpus_info(corpus) if corpus is not None else (0, 0, 0)
     _log("corpus automaton: %d states, %d transitions, %.1f MB on device, built in %.1f s"
@@ -236,7 +247,14 @@ def cpu_leg(w):
         corpus = corpus[:limit]
         note = "; corpus cut to its first %d tokens to bound the run" % limit
     t0 = time.time()
-    static = Sam.build(corpus) if corpus is not None else None
+    said = [t0]
+
+    def progress(done, total):
+        if time.time() - said[0] > 20.0:
+            said[0] = time.time()
+            _log("CPU checker, corpus build: %d of %d" % (done, total))
+
+    static = Sam.build(corpus, progress=progress) if corpus is not None else None
     build_s = time.time() - t0
     nb = min(spec.batch, 64)
     ob = Batch(static, corpus, [w.prompts[b] for b in range(nb)], spec.max_accept,
