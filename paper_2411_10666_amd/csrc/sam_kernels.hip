@@ -343,6 +343,7 @@ struct DynCursor {
     uint32_t n, n_states, last, n_trans;
     uint32_t P;               // link(last); kNil while the sequence is empty
     Rec      RP;              // record of P, kept in step with memory
+    uint32_t rec_bytes;       // size of the sequence's record table
     bool     pf_ok;           // pf is the reduced home bucket of (P, next token)
     Probe<L> pf;
 };
@@ -509,6 +510,431 @@ __device__ __forceinline__ void flush_last(const DynSeq &D, const DynCursor<L> &
     if (lane == 0) L::store_rec(D.rec, c.last, LR);
 }
 
+// ---- compact layout: Expand (Algorithm 2) in gfx950 assembly ----------------
+//
+// The same algorithm as dyn_expand above, for the compact tables, written out by
+// hand: one wavefront's dependent instruction chain is what a token costs, and
+// this form needs about half the instructions of the compiled one (records stay
+// packed as stored, no copies between paths, stores under a one-lane exec mask
+// without a branch).  The wide layout and a sequence's very first token take the
+// C++ path.  Every table access goes through a buffer resource whose size is
+// the table's, so an index outside a table reads zeros or is dropped instead of
+// touching foreign memory, and every loop that follows table contents counts
+// down a guard.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ u32x4 table_rsrc(const void *base, uint32_t bytes)
+{
+    const uint64_t a = (uint64_t)base;
+    u32x4 r;
+    r.x = uni((uint32_t)a);
+    r.y = uni((uint32_t)(a >> 32)) & 0xFFFFu;   // stride 0: raw buffer
+    r.z = bytes;
+    r.w = 0x00020000u;                          // 32-bit data format
+    return r;
+}
+
+// Append tokens tv[i .. m) to a sequence whose cursor is not at its very first
+// token (P is a state).  i: index of the next token (in/out); on return i == m,
+// or tv[i] is outside the vocabulary, or `flt` carries the internal-error bit.
+// r0..r3 are the record of P as stored in the table.
+//
+// Register use inside (all named registers are scratch for this block):
+//   s64 t        s65 next token (-1: none)   s66 t * c2      s67 i + 1
+//   s68 q        s69..s71 scratch            s72 probe bucket (-1: no probe held)
+//   s73 probe hit mask   s74 probe empty mask   s75 bucket of (q, next token)
+//   s76..s79 record of q        s80 s81 words 0, 1 of last's record   s82 cur
+//   s83 where the transition to q sits (slot index, -2: inline)   s84 slot index
+//   s85 key      s86 loop guard   s87 last before this token   s88 clone
+//   s89..s92 record of the clone  s93 list cursor  s94 token of a copied slot
+//   s95 its target
+//   v40 v41 addresses   v42:43 probe bucket   v44:45 next token's bucket
+//   v46:49 record load  v50:53 store data  v54 store data of 16-bit fields   s96:97 exec on entry
+// The probe of a bucket: lanes 0..15 load its 16 slots; hit mask = lanes whose
+// key matches, empty mask = lanes whose key is the empty key.
+#define SAM_HASH(dst, state, tokmul)                                                  \
+        "s_mul_i32 s69, " state ", 0x9e3779b1\n\t"                                    \
+        "s_xor_b32 s69, s69, " tokmul "\n\t"                                          \
+        "s_lshr_b32 s70, s69, 15\n\t"                                                 \
+        "s_xor_b32 s69, s69, s70\n\t"                                                 \
+        "s_mul_i32 s69, s69, 0x2c1b3c6d\n\t"                                          \
+        "s_mul_hi_u32 " dst ", s69, %[nb]\n\t"
+#define SAM_LOAD_BUCKET(vdst, bucket)                                                 \
+        "s_lshl_b32 s69, " bucket ", 7\n\t"                                           \
+        "v_add_u32 v41, s69, %[lo]\n\t"                                               \
+        "buffer_load_dwordx2 " vdst ", v41, %[rslt], 0 offen\n\t"
+#define SAM_NEXT_BUCKET(bucket)                                                       \
+        "s_add_u32 " bucket ", " bucket ", 1\n\t"                                     \
+        "s_cmp_eq_u32 " bucket ", %[nb]\n\t"                                          \
+        "s_cselect_b32 " bucket ", 0, " bucket "\n\t"
+#define SAM_GUARD(label)                                                              \
+        "s_sub_u32 s86, s86, 1\n\t"                                                   \
+        "s_cbranch_scc1 " label "\n\t"
+// record of P and home bucket of (P, t) in one round trip -> r0..r3, s72..s74
+#define SAM_REC_AND_PROBE                                                             \
+        "s_lshl_b32 s70, %[P], 4\n\t"                                                 \
+        "v_mov_b32 v40, s70\n\t"                                                      \
+        "buffer_load_dwordx4 v[46:49], v40, %[rrec], 0 offen\n\t"                     \
+        SAM_HASH("s72", "%[P]", "s66")                                                \
+        SAM_LOAD_BUCKET("v[42:43]", "s72")                                            \
+        "s_lshl_b32 s85, %[P], 17\n\t"                                                \
+        "s_or_b32 s85, s85, s64\n\t"                                                  \
+        "s_waitcnt vmcnt(0)\n\t"                                                      \
+        "v_cmp_eq_u32 vcc, s85, v42\n\t"                                              \
+        "v_cmp_eq_u32 s[70:71], -1, v42\n\t"                                          \
+        "v_readfirstlane_b32 %[r0], v46\n\t"                                          \
+        "v_readfirstlane_b32 %[r1], v47\n\t"                                          \
+        "v_readfirstlane_b32 %[r2], v48\n\t"                                          \
+        "v_readfirstlane_b32 %[r3], v49\n\t"                                          \
+        "s_mov_b32 s73, vcc_lo\n\t"                                                   \
+        "s_mov_b32 s74, s70\n\t"
+
+__device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_t nb, uint32_t m,
+                                                 uint32_t vocab, uint32_t tv, uint32_t lo,
+                                                 uint32_t &i, uint32_t &n, uint32_t &ns,
+                                                 uint32_t &last, uint32_t &nt, uint32_t &P,
+                                                 uint32_t &r0, uint32_t &r1, uint32_t &r2,
+                                                 uint32_t &r3, uint32_t &flt)
+{
+    asm volatile(
+        "s_mov_b64 s[96:97], exec\n\t"
+        "s_mov_b64 exec, 0xffff\n\t"
+        "s_mov_b32 s72, -1\n"
+        // ---- one token ---------------------------------------------------------
+        "L_token_%=:\n\t"
+        "v_readlane_b32 s64, %[tv], %[i]\n\t"
+        "s_add_u32 s67, %[i], 1\n\t"
+        "s_mov_b32 s65, -1\n\t"
+        "s_cmp_ge_u32 s64, %[vocab]\n\t"
+        "s_cbranch_scc1 L_exit_%=\n\t"
+        "s_mul_i32 s66, s64, 0x85ebca77\n\t"
+        "s_cmp_lt_u32 s67, %[m]\n\t"
+        "s_cbranch_scc0 L_notn_%=\n\t"
+        "v_readlane_b32 s65, %[tv], s67\n\t"
+        "s_cmp_lt_u32 s65, %[vocab]\n\t"
+        "s_cselect_b32 s65, s65, -1\n"
+        "L_notn_%=:\n\t"
+        // new state cur; last's record {n | P << 16, n | none << 16, t, cur}
+        "s_mov_b32 s82, %[ns]\n\t"
+        "s_lshl_b32 s80, %[P], 16\n\t"
+        "s_or_b32 s80, s80, %[n]\n\t"
+        "s_or_b32 s81, %[n], 0xffff0000\n\t"
+        "s_lshl_b32 s69, %[last], 4\n\t"
+        "s_mov_b64 exec, 1\n\t"
+        "v_mov_b32 v40, s69\n\t"
+        "v_mov_b32 v50, s80\n\t"
+        "v_mov_b32 v51, s81\n\t"
+        "v_mov_b32 v52, s64\n\t"
+        "v_mov_b32 v53, s82\n\t"
+        "buffer_store_dwordx4 v[50:53], v40, %[rrec], 0 offen\n\t"
+        "s_mov_b64 exec, 0xffff\n\t"
+        "s_add_u32 %[ns], %[ns], 1\n\t"
+        "s_add_u32 %[nt], %[nt], 1\n\t"
+        "s_add_u32 %[n], %[n], 1\n\t"
+        "s_mov_b32 s87, %[last]\n\t"
+        "s_mov_b32 %[last], s82\n\t"
+        "s_add_u32 s86, %[ns], 4\n"
+        // ---- walk last's suffix path: states without a t-transition get one ----
+        "L_walk_%=:\n\t"
+        SAM_GUARD("L_corrupt_%=")
+        "s_cmp_eq_u32 %[r2], s64\n\t"
+        "s_cbranch_scc1 L_inline_%=\n\t"
+        "s_cmp_eq_u32 s72, -1\n\t"
+        "s_cbranch_scc0 L_resolve_%=\n\t"
+        // no probe held for (P, t): fetch and reduce its home bucket
+        SAM_HASH("s72", "%[P]", "s66")
+        SAM_LOAD_BUCKET("v[42:43]", "s72")
+        "s_lshl_b32 s85, %[P], 17\n\t"
+        "s_or_b32 s85, s85, s64\n\t"
+        "s_waitcnt vmcnt(0)\n\t"
+        "v_cmp_eq_u32 vcc, s85, v42\n\t"
+        "v_cmp_eq_u32 s[70:71], -1, v42\n\t"
+        "s_mov_b32 s73, vcc_lo\n\t"
+        "s_mov_b32 s74, s70\n"
+        "L_resolve_%=:\n\t"
+        "s_cmp_lg_u32 s73, 0\n\t"
+        "s_cbranch_scc1 L_hit_%=\n\t"
+        "s_cmp_lg_u32 s74, 0\n\t"
+        "s_cbranch_scc1 L_miss_%=\n\t"
+        // bucket full of other keys: go on in the next one
+        SAM_GUARD("L_corrupt_%=")
+        SAM_NEXT_BUCKET("s72")
+        SAM_LOAD_BUCKET("v[42:43]", "s72")
+        "s_lshl_b32 s85, %[P], 17\n\t"
+        "s_or_b32 s85, s85, s64\n\t"
+        "s_waitcnt vmcnt(0)\n\t"
+        "v_cmp_eq_u32 vcc, s85, v42\n\t"
+        "v_cmp_eq_u32 s[70:71], -1, v42\n\t"
+        "s_mov_b32 s73, vcc_lo\n\t"
+        "s_mov_b32 s74, s70\n\t"
+        "s_branch L_resolve_%=\n"
+        "L_hit_%=:\n\t"
+        "s_ff1_i32_b32 s69, s73\n\t"
+        "v_readlane_b32 s68, v43, s69\n\t"
+        "s_lshl_b32 s83, s72, 4\n\t"
+        "s_add_u32 s83, s83, s69\n\t"
+        "s_and_b32 s68, s68, 0xffff\n\t"
+        "s_branch L_found_%=\n"
+        "L_inline_%=:\n\t"
+        "s_mov_b32 s68, %[r3]\n\t"
+        "s_mov_b32 s83, -2\n\t"
+        "s_branch L_found_%=\n"
+        "L_miss_%=:\n\t"
+        // (P, t) -> cur: inline if P has no transition yet, else into the empty slot
+        "s_cmp_eq_u32 %[r2], -1\n\t"
+        "s_cbranch_scc1 L_ins_inline_%=\n\t"
+        "s_ff1_i32_b32 s69, s74\n\t"
+        "s_lshl_b32 s84, s72, 4\n\t"
+        "s_add_u32 s84, s84, s69\n\t"
+        "s_lshl_b32 s85, %[P], 17\n\t"
+        "s_or_b32 s85, s85, s64\n\t"
+        "s_and_b32 s70, %[r1], 0xffff0000\n\t"
+        "s_or_b32 s70, s70, s82\n\t"
+        "s_lshl_b32 s69, s84, 3\n\t"
+        "s_lshl_b32 s71, %[P], 4\n\t"
+        "s_mov_b64 exec, 1\n\t"
+        "v_mov_b32 v40, s69\n\t"
+        "v_mov_b32 v50, s85\n\t"
+        "v_mov_b32 v51, s70\n\t"
+        "buffer_store_dwordx2 v[50:51], v40, %[rslt], 0 offen\n\t"
+        "v_mov_b32 v41, s71\n\t"
+        "v_mov_b32 v52, s84\n\t"
+        "buffer_store_short v52, v41, %[rrec], 0 offen offset:6\n\t"
+        "s_mov_b64 exec, 0xffff\n\t"
+        "s_and_b32 %[r1], %[r1], 0xffff\n\t"
+        "s_lshl_b32 s69, s84, 16\n\t"
+        "s_or_b32 %[r1], %[r1], s69\n\t"
+        "s_branch L_inserted_%=\n"
+        "L_ins_inline_%=:\n\t"
+        "s_lshl_b32 s71, %[P], 4\n\t"
+        "s_mov_b64 exec, 1\n\t"
+        "v_mov_b32 v41, s71\n\t"
+        "v_mov_b32 v50, s64\n\t"
+        "v_mov_b32 v51, s82\n\t"
+        "buffer_store_dwordx2 v[50:51], v41, %[rrec], 0 offen offset:8\n\t"
+        "s_mov_b64 exec, 0xffff\n\t"
+        "s_mov_b32 %[r2], s64\n\t"
+        "s_mov_b32 %[r3], s82\n"
+        "L_inserted_%=:\n\t"
+        "s_add_u32 %[nt], %[nt], 1\n\t"
+        "s_lshr_b32 s69, %[r0], 16\n\t"
+        "s_mov_b32 s72, -1\n\t"
+        "s_cmp_eq_u32 s69, 0xffff\n\t"
+        "s_cbranch_scc1 L_next_%=\n\t"          // P is the root: it stays the cursor
+        "s_mov_b32 %[P], s69\n\t"
+        SAM_REC_AND_PROBE
+        "s_branch L_walk_%=\n"
+        // ---- q = next(P)[t] exists -----------------------------------------------
+        "L_found_%=:\n\t"
+        "s_lshl_b32 s69, s68, 4\n\t"
+        "v_mov_b32 v40, s69\n\t"
+        "buffer_load_dwordx4 v[46:49], v40, %[rrec], 0 offen\n\t"
+        "s_cmp_eq_u32 s65, -1\n\t"
+        "s_cbranch_scc1 L_noprefetch_%=\n\t"
+        // with it, the next token's first lookup (at q)
+        "s_mul_i32 s71, s65, 0x85ebca77\n\t"
+        SAM_HASH("s75", "s68", "s71")
+        SAM_LOAD_BUCKET("v[44:45]", "s75")
+        "s_waitcnt vmcnt(1)\n\t"
+        "s_branch L_qrec_%=\n"
+        "L_noprefetch_%=:\n\t"
+        "s_waitcnt vmcnt(0)\n"
+        "L_qrec_%=:\n\t"
+        "v_readfirstlane_b32 s76, v46\n\t"
+        "v_readfirstlane_b32 s77, v47\n\t"
+        "v_readfirstlane_b32 s78, v48\n\t"
+        "v_readfirstlane_b32 s79, v49\n\t"
+        "s_cmp_lg_u32 s68, s87\n\t"
+        "s_cbranch_scc1 L_qok_%=\n\t"
+        "s_mov_b32 s76, s80\n\t"                // q is the old last: its record as just written
+        "s_mov_b32 s77, s81\n\t"
+        "s_mov_b32 s78, s64\n\t"
+        "s_mov_b32 s79, s82\n"
+        "L_qok_%=:\n\t"
+        "s_and_b32 s69, %[r0], 0xffff\n\t"
+        "s_add_u32 s69, s69, 1\n\t"             // len(P) + 1
+        "s_and_b32 s70, s76, 0xffff\n\t"
+        "s_cmp_eq_u32 s69, s70\n\t"
+        "s_cbranch_scc0 L_clone_%=\n\t"
+        "s_mov_b32 %[P], s68\n\t"
+        "s_mov_b32 %[r0], s76\n\t"
+        "s_mov_b32 %[r1], s77\n\t"
+        "s_mov_b32 %[r2], s78\n\t"
+        "s_mov_b32 %[r3], s79\n\t"
+        "s_mov_b32 s72, -1\n\t"
+        "s_cmp_eq_u32 s65, -1\n\t"
+        "s_cbranch_scc1 L_next_%=\n\t"
+        "s_lshl_b32 s85, s68, 17\n\t"
+        "s_or_b32 s85, s85, s65\n\t"
+        "s_mov_b32 s72, s75\n\t"
+        "s_waitcnt vmcnt(0)\n\t"
+        "v_mov_b32 v42, v44\n\t"
+        "v_mov_b32 v43, v45\n\t"
+        "v_cmp_eq_u32 vcc, s85, v44\n\t"
+        "v_cmp_eq_u32 s[70:71], -1, v44\n\t"
+        "s_mov_b32 s73, vcc_lo\n\t"
+        "s_mov_b32 s74, s70\n\t"
+        "s_branch L_next_%=\n"
+        // ---- clone q at length len(P) + 1 ------------------------------------------
+        "L_clone_%=:\n\t"
+        "s_mov_b32 s88, %[ns]\n\t"
+        "s_add_u32 %[ns], %[ns], 1\n\t"
+        "s_and_b32 s89, s76, 0xffff0000\n\t"
+        "s_or_b32 s89, s89, s69\n\t"            // len = len(P) + 1, link = link(q)
+        "s_or_b32 s90, s77, 0xffff0000\n\t"     // endpos(q), empty list
+        "s_mov_b32 s91, s78\n\t"
+        "s_mov_b32 s92, s79\n\t"
+        "s_lshr_b32 s93, s77, 16\n\t"           // head of q's list
+        "s_waitcnt vmcnt(0)\n\t"
+        "s_cmp_eq_u32 s78, -1\n\t"
+        "s_cbranch_scc1 L_copy_%=\n\t"
+        "s_add_u32 %[nt], %[nt], 1\n"
+        "L_copy_%=:\n\t"
+        "s_cmp_eq_u32 s93, 0xffff\n\t"
+        "s_cbranch_scc1 L_copied_%=\n\t"
+        SAM_GUARD("L_corrupt_%=")
+        "s_lshl_b32 s69, s93, 3\n\t"
+        "v_mov_b32 v40, s69\n\t"
+        "buffer_load_dwordx2 v[46:47], v40, %[rslt], 0 offen\n\t"
+        "s_waitcnt vmcnt(0)\n\t"
+        "v_readfirstlane_b32 s94, v46\n\t"
+        "v_readfirstlane_b32 s95, v47\n\t"
+        "s_and_b32 s94, s94, 0x1ffff\n\t"
+        "s_lshr_b32 s93, s95, 16\n\t"
+        "s_and_b32 s95, s95, 0xffff\n\t"
+        "s_mul_i32 s71, s94, 0x85ebca77\n\t"
+        SAM_HASH("s84", "s88", "s71")
+        "L_copy_probe_%=:\n\t"
+        SAM_LOAD_BUCKET("v[42:43]", "s84")
+        "s_waitcnt vmcnt(0)\n\t"
+        "v_cmp_eq_u32 vcc, -1, v42\n\t"
+        "s_nop 1\n\t"
+        "s_cmp_lg_u32 vcc_lo, 0\n\t"
+        "s_cbranch_scc1 L_copy_put_%=\n\t"
+        SAM_GUARD("L_corrupt_%=")
+        SAM_NEXT_BUCKET("s84")
+        "s_branch L_copy_probe_%=\n"
+        "L_copy_put_%=:\n\t"
+        "s_ff1_i32_b32 s69, vcc_lo\n\t"
+        "s_lshl_b32 s84, s84, 4\n\t"
+        "s_add_u32 s84, s84, s69\n\t"           // slot index
+        "s_lshl_b32 s85, s88, 17\n\t"
+        "s_or_b32 s85, s85, s94\n\t"
+        "s_and_b32 s70, s90, 0xffff0000\n\t"
+        "s_or_b32 s70, s70, s95\n\t"
+        "s_lshl_b32 s69, s84, 3\n\t"
+        "s_mov_b64 exec, 1\n\t"
+        "v_mov_b32 v40, s69\n\t"
+        "v_mov_b32 v50, s85\n\t"
+        "v_mov_b32 v51, s70\n\t"
+        "buffer_store_dwordx2 v[50:51], v40, %[rslt], 0 offen\n\t"
+        "s_mov_b64 exec, 0xffff\n\t"
+        "s_and_b32 s90, s90, 0xffff\n\t"
+        "s_lshl_b32 s69, s84, 16\n\t"
+        "s_or_b32 s90, s90, s69\n\t"
+        "s_add_u32 %[nt], %[nt], 1\n\t"
+        "s_branch L_copy_%=\n"
+        "L_copied_%=:\n\t"
+        "s_lshl_b32 s69, s88, 4\n\t"
+        "s_mov_b64 exec, 1\n\t"
+        "v_mov_b32 v40, s69\n\t"
+        "v_mov_b32 v50, s89\n\t"
+        "v_mov_b32 v51, s90\n\t"
+        "v_mov_b32 v52, s91\n\t"
+        "v_mov_b32 v53, s92\n\t"
+        "buffer_store_dwordx4 v[50:53], v40, %[rrec], 0 offen\n\t"
+        "s_mov_b64 exec, 0xffff\n"
+        // states further up the path that still lead to q now lead to the clone
+        "L_redirect_%=:\n\t"
+        "s_mov_b64 exec, 1\n\t"
+        "v_mov_b32 v54, s88\n\t"
+        "s_cmp_eq_u32 s83, -2\n\t"
+        "s_cbranch_scc0 L_red_slot_%=\n\t"
+        "s_lshl_b32 s69, %[P], 4\n\t"
+        "v_mov_b32 v40, s69\n\t"
+        "buffer_store_short v54, v40, %[rrec], 0 offen offset:12\n\t"
+        "s_branch L_red_up_%=\n"
+        "L_red_slot_%=:\n\t"
+        "s_lshl_b32 s69, s83, 3\n\t"
+        "v_mov_b32 v40, s69\n\t"
+        "buffer_store_short v54, v40, %[rslt], 0 offen offset:4\n"
+        "L_red_up_%=:\n\t"
+        "s_mov_b64 exec, 0xffff\n\t"
+        "s_lshr_b32 s69, %[r0], 16\n\t"
+        "s_cmp_eq_u32 s69, 0xffff\n\t"
+        "s_cbranch_scc1 L_redirected_%=\n\t"
+        SAM_GUARD("L_corrupt_%=")
+        "s_mov_b32 %[P], s69\n\t"
+        SAM_REC_AND_PROBE
+        "s_cmp_eq_u32 %[r2], s64\n\t"
+        "s_cbranch_scc0 L_red_resolve_%=\n\t"
+        "s_cmp_eq_u32 %[r3], s68\n\t"
+        "s_cbranch_scc0 L_redirected_%=\n\t"
+        "s_mov_b32 s83, -2\n\t"
+        "s_branch L_redirect_%=\n"
+        "L_red_resolve_%=:\n\t"
+        "s_cmp_lg_u32 s73, 0\n\t"
+        "s_cbranch_scc1 L_red_hit_%=\n\t"
+        "s_cmp_lg_u32 s74, 0\n\t"
+        "s_cbranch_scc1 L_redirected_%=\n\t"
+        SAM_GUARD("L_corrupt_%=")
+        SAM_NEXT_BUCKET("s72")
+        SAM_LOAD_BUCKET("v[42:43]", "s72")
+        "s_waitcnt vmcnt(0)\n\t"
+        "v_cmp_eq_u32 vcc, s85, v42\n\t"
+        "v_cmp_eq_u32 s[70:71], -1, v42\n\t"
+        "s_mov_b32 s73, vcc_lo\n\t"
+        "s_mov_b32 s74, s70\n\t"
+        "s_branch L_red_resolve_%=\n"
+        "L_red_hit_%=:\n\t"
+        "s_ff1_i32_b32 s69, s73\n\t"
+        "v_readlane_b32 s70, v43, s69\n\t"
+        "s_lshl_b32 s83, s72, 4\n\t"
+        "s_add_u32 s83, s83, s69\n\t"
+        "s_and_b32 s70, s70, 0xffff\n\t"
+        "s_cmp_eq_u32 s70, s68\n\t"
+        "s_cbranch_scc1 L_redirect_%=\n"
+        "L_redirected_%=:\n\t"
+        "s_lshl_b32 s69, s68, 4\n\t"
+        "s_mov_b64 exec, 1\n\t"
+        "v_mov_b32 v40, s69\n\t"
+        "v_mov_b32 v54, s88\n\t"
+        "buffer_store_short v54, v40, %[rrec], 0 offen offset:2\n\t"
+        "s_mov_b64 exec, 0xffff\n\t"
+        "s_mov_b32 %[P], s88\n\t"
+        "s_mov_b32 %[r0], s89\n\t"
+        "s_mov_b32 %[r1], s90\n\t"
+        "s_mov_b32 %[r2], s91\n\t"
+        "s_mov_b32 %[r3], s92\n\t"
+        "s_mov_b32 s72, -1\n"
+        // ---- next token -------------------------------------------------------------
+        "L_next_%=:\n\t"
+        "s_mov_b32 %[i], s67\n\t"
+        "s_cmp_lt_u32 %[i], %[m]\n\t"
+        "s_cbranch_scc1 L_token_%=\n\t"
+        "s_branch L_exit_%=\n"
+        "L_corrupt_%=:\n\t"
+        "s_or_b32 %[flt], %[flt], 8\n"
+        "L_exit_%=:\n\t"
+        "s_waitcnt vmcnt(0)\n\t"
+        "s_mov_b64 exec, s[96:97]\n\t"
+        : [i] "+s"(i), [n] "+s"(n), [ns] "+s"(ns), [last] "+s"(last), [nt] "+s"(nt), [P] "+s"(P),
+          [r0] "+s"(r0), [r1] "+s"(r1), [r2] "+s"(r2), [r3] "+s"(r3), [flt] "+s"(flt)
+        : [rrec] "s"(rrec), [rslt] "s"(rslt), [nb] "s"(nb), [m] "s"(m), [vocab] "s"(vocab),
+          [tv] "v"(tv), [lo] "v"(lo)
+        : "memory", "vcc", "scc",
+          "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", "s72", "s73", "s74", "s75",
+          "s76", "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87",
+          "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", "s96", "s97",
+          "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", "v50", "v51",
+          "v52", "v53", "v54");
+}
+#undef SAM_HASH
+#undef SAM_LOAD_BUCKET
+#undef SAM_NEXT_BUCKET
+#undef SAM_GUARD
+#undef SAM_REC_AND_PROBE
+
 // ---- per-wave work shared by the step, ingest and replay kernels -------------
 
 // Wave 0: feed `count` tokens to the static cursor; stops in front of a token
@@ -544,15 +970,52 @@ __device__ __forceinline__ void dyn_feed(const DynSeq &D, const int32_t *tok, in
         c.pf_ok = false;
         const uint32_t n_chunk = c.n;
         int fed = 0;
-        for (; fed < m; fed++) {
-            const uint32_t t = lane_get(tv, fed);
-            if (t >= vocab) { stop = true; fault |= SAM_STATUS_TOKEN_BIT; break; }
-            uint32_t tn = kNil;
-            if (fed + 1 < m) {
-                tn = lane_get(tv, fed + 1);
-                if (tn >= vocab) tn = kNil;
+        if constexpr (L::kSlots == 16) {
+            // values the two waves of a workgroup hold jointly count as per-lane for
+            // the compiler; the assembly wants them in scalar registers
+            const uint32_t nbk = uni(D.n_buckets), m_u = uni((uint32_t)m), vocab_u = uni(vocab);
+            const u32x4 rrec = table_rsrc(D.rec, uni(c.rec_bytes));
+            const u32x4 rslt = table_rsrc(D.slots, nbk * 128u);
+            c.n = uni(c.n); c.n_states = uni(c.n_states); c.last = uni(c.last);
+            c.n_trans = uni(c.n_trans); c.P = uni(c.P);
+            const uint32_t lo = (uint32_t)(lane & 15) * 8u;
+            if (c.P == kNil && m > 0) {
+                // the sequence's very first token
+                const uint32_t t = lane_get(tv, 0);
+                if (t >= vocab) { stop = true; fault |= SAM_STATUS_TOKEN_BIT; }
+                else { dyn_expand<L>(D, t, kNil, lane, c, fault); fed = 1; }
             }
-            dyn_expand<L>(D, t, tn, lane, c, fault);
+            if (!stop && fed < m) {
+                uint32_t i = uni((uint32_t)fed), flt = 0;
+                uint32_t r0 = uni((c.RP.len & 0xFFFFu) | (c.RP.link << 16));
+                uint32_t r1 = uni((c.RP.endpos & 0xFFFFu) | (c.RP.head << 16));
+                uint32_t r2 = uni(c.RP.itok), r3 = uni(c.RP.idst & 0xFFFFu);
+                uint32_t a_n = uni(c.n), a_ns = uni(c.n_states), a_last = uni(c.last);
+                uint32_t a_nt = uni(c.n_trans), a_P = uni(c.P);
+                dyn_feed_compact(rrec, rslt, nbk, m_u, vocab_u, tv, lo, i, a_n, a_ns, a_last,
+                                 a_nt, a_P, r0, r1, r2, r3, flt);
+                c.n = a_n; c.n_states = a_ns; c.last = a_last; c.n_trans = a_nt; c.P = a_P;
+                c.RP.len = r0 & 0xFFFFu; c.RP.link = L::widen(r0 >> 16);
+                c.RP.endpos = r1 & 0xFFFFu; c.RP.head = L::widen(r1 >> 16);
+                c.RP.itok = r2; c.RP.idst = r3;
+                fed = (int)i;
+                fault |= flt;
+                if (fed < m) {
+                    stop = true;
+                    if (!flt) fault |= SAM_STATUS_TOKEN_BIT;
+                }
+            }
+        } else {
+            for (; fed < m; fed++) {
+                const uint32_t t = lane_get(tv, fed);
+                if (t >= vocab) { stop = true; fault |= SAM_STATUS_TOKEN_BIT; break; }
+                uint32_t tn = kNil;
+                if (fed + 1 < m) {
+                    tn = lane_get(tv, fed + 1);
+                    if (tn >= vocab) tn = kNil;
+                }
+                dyn_expand<L>(D, t, tn, lane, c, fault);
+            }
         }
         // the sequence's text, one coalesced store per chunk
         if (lane < fed) D.text[n_chunk + lane] = (int32_t)tv;
@@ -580,6 +1043,7 @@ __device__ __forceinline__ void load_cursor(const SeqMeta *meta, DynCursor<L> &c
     c.RP.len = uni(meta->p_len); c.RP.link = uni(meta->p_link);
     c.RP.endpos = uni(meta->p_endpos); c.RP.head = uni(meta->p_head);
     c.RP.itok = uni(meta->p_itok); c.RP.idst = uni(meta->p_idst);
+    c.rec_bytes = 0;
     c.pf_ok = false;
     c.pf.b = 0; c.pf.mh = 0; c.pf.me = 0;
     c.pf.sl = typename L::RawSlot();
@@ -674,6 +1138,7 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
         const DynSeq D = dyn_region<L>(B, b);
         DynCursor<L> c;
         load_cursor<L>(meta, c);
+        c.rec_bytes = (uint32_t)B.max_states * 16u;
         dyn_feed<L>(D, tok, count, vocab, lane, c, fault);
         if (c.n != n0) flush_last<L>(D, c, lane);
         if (lane == 0) {
@@ -731,6 +1196,7 @@ __global__ __launch_bounds__(128) void sam_replay_kernel(StaticView S, BatchView
     DynCursor<L> c;
     if (wave == 0) { s = uni(meta->s1); l = uni(meta->l1); e = uni(meta->e1); }
     load_cursor<L>(meta, c);
+    c.rec_bytes = (uint32_t)B.max_states * 16u;
     const uint32_t n_first = n_cur;
 
     for (int step = 0; step < n_steps; step++) {
