@@ -937,6 +937,128 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
 
 // ---- per-wave work shared by the step, ingest and replay kernels -------------
 
+// Transfer (Algorithm 1) over tokens tv[i .. m) in gfx950 assembly: the same
+// steps as static_transfer, about a third of the instructions.  Lanes 0..7 fetch
+// the 8 slots of a bucket, the suffix-link record travels with the bucket.  i:
+// index of the next token (in/out); on return i == m or tv[i] is outside the
+// vocabulary.  Needs n_buckets < 2^32.
+//   s64 t   s65 t * c2   s66 link-hop guard   s67 bucket-sweep guard
+//   s68:69 s70:71 addresses / compare results   s72 hash   s73 bucket
+//   s74 hit mask   s75 empty mask   s76:77 compare result   s78 s79 scratch
+//   v41 zero   v42:45 slot {state, token, dst, endpos}   v46:47 link record / root entry
+__device__ __forceinline__ void static_feed_asm(uint32_t slots_lo, uint32_t slots_hi,
+                                                uint32_t lr_lo, uint32_t lr_hi, uint32_t root_lo,
+                                                uint32_t root_hi, uint32_t nb, uint32_t m,
+                                                uint32_t vocab, uint32_t tv, uint32_t lane16,
+                                                uint32_t &i, uint32_t &st, uint32_t &l,
+                                                uint32_t &e, uint32_t &flt)
+{
+    asm volatile(
+        "s_mov_b64 s[96:97], exec\n\t"
+        "s_mov_b64 exec, 0xff\n\t"
+        "v_mov_b32 v41, 0\n"
+        "L_stok_%=:\n\t"
+        "v_readlane_b32 s64, %[tv], %[i]\n\t"
+        "s_add_u32 s66, %[l], 2\n\t"            // every link hop shortens the match
+        "s_cmp_ge_u32 s64, %[vocab]\n\t"
+        "s_cbranch_scc1 L_sexit_%=\n\t"
+        "s_mul_i32 s65, s64, 0x85ebca77\n"
+        "L_stry_%=:\n\t"
+        "s_sub_u32 s66, s66, 1\n\t"
+        "s_cbranch_scc1 L_scorrupt_%=\n\t"
+        "s_cmp_eq_u32 %[st], 0\n\t"
+        "s_cbranch_scc1 L_sroot_%=\n\t"
+        // suffix-link record of the state, in flight together with the bucket
+        "s_lshl_b32 s68, %[st], 3\n\t"
+        "s_lshr_b32 s69, %[st], 29\n\t"
+        "s_add_u32 s68, s68, %[lr_lo]\n\t"
+        "s_addc_u32 s69, s69, %[lr_hi]\n\t"
+        "global_load_dwordx2 v[46:47], v41, s[68:69]\n\t"
+        "s_mul_i32 s72, %[st], 0x9e3779b1\n\t"
+        "s_add_u32 s72, s72, s65\n\t"
+        "s_lshr_b32 s79, s72, 15\n\t"
+        "s_xor_b32 s72, s72, s79\n\t"
+        "s_mul_i32 s72, s72, 0x2c1b3c6d\n\t"
+        "s_lshr_b32 s79, s72, 12\n\t"
+        "s_xor_b32 s72, s72, s79\n\t"
+        "s_mul_i32 s72, s72, 0x297a2d39\n\t"
+        "s_lshr_b32 s79, s72, 15\n\t"
+        "s_xor_b32 s72, s72, s79\n\t"
+        "s_mul_hi_u32 s73, s72, %[nb]\n\t"
+        "s_mov_b32 s67, %[nb]\n"
+        "L_sload_%=:\n\t"
+        "s_lshl_b32 s70, s73, 7\n\t"
+        "s_lshr_b32 s71, s73, 25\n\t"
+        "s_add_u32 s70, s70, %[slots_lo]\n\t"
+        "s_addc_u32 s71, s71, %[slots_hi]\n\t"
+        "global_load_dwordx4 v[42:45], %[lane16], s[70:71]\n\t"
+        "s_waitcnt vmcnt(0)\n\t"
+        "v_cmp_eq_u32 vcc, %[st], v42\n\t"
+        "v_cmp_eq_u32 s[76:77], s64, v43\n\t"
+        "v_cmp_eq_u32 s[70:71], -1, v42\n\t"
+        "s_and_b32 s74, vcc_lo, s76\n\t"
+        "s_mov_b32 s75, s70\n\t"
+        "s_cmp_lg_u32 s74, 0\n\t"
+        "s_cbranch_scc1 L_shit_%=\n\t"
+        "s_cmp_lg_u32 s75, 0\n\t"
+        "s_cbranch_scc1 L_smiss_%=\n\t"
+        // bucket full of other keys: go on in the next one
+        "s_sub_u32 s67, s67, 1\n\t"
+        "s_cbranch_scc1 L_scorrupt_%=\n\t"
+        "s_add_u32 s73, s73, 1\n\t"
+        "s_cmp_eq_u32 s73, %[nb]\n\t"
+        "s_cselect_b32 s73, 0, s73\n\t"
+        "s_branch L_sload_%=\n"
+        "L_shit_%=:\n\t"
+        "s_ff1_i32_b32 s78, s74\n\t"
+        "s_add_u32 %[l], %[l], 1\n\t"
+        "v_readlane_b32 %[st], v44, s78\n\t"
+        "v_readlane_b32 %[e], v45, s78\n\t"
+        "s_branch L_sdone_%=\n"
+        "L_smiss_%=:\n\t"
+        "v_readfirstlane_b32 %[st], v46\n\t"    // follow the suffix link
+        "v_readfirstlane_b32 %[l], v47\n\t"
+        "s_branch L_stry_%=\n"
+        "L_sroot_%=:\n\t"
+        "s_lshl_b32 s68, s64, 3\n\t"
+        "s_add_u32 s68, s68, %[root_lo]\n\t"
+        "s_addc_u32 s69, %[root_hi], 0\n\t"
+        "global_load_dwordx2 v[46:47], v41, s[68:69]\n\t"
+        "s_waitcnt vmcnt(0)\n\t"
+        "v_readfirstlane_b32 s78, v46\n\t"
+        "v_readfirstlane_b32 s79, v47\n\t"
+        "s_cmp_eq_u32 s78, 0\n\t"
+        "s_cbranch_scc1 L_snone_%=\n\t"
+        "s_mov_b32 %[st], s78\n\t"
+        "s_mov_b32 %[e], s79\n\t"
+        "s_mov_b32 %[l], 1\n\t"
+        "s_branch L_sdone_%=\n"
+        "L_snone_%=:\n\t"
+        "s_mov_b32 %[l], 0\n\t"
+        "s_mov_b32 %[e], 0\n"
+        "L_sdone_%=:\n\t"
+        "s_add_u32 %[i], %[i], 1\n\t"
+        "s_cmp_lt_u32 %[i], %[m]\n\t"
+        "s_cbranch_scc1 L_stok_%=\n\t"
+        "s_branch L_sexit_%=\n"
+        "L_scorrupt_%=:\n\t"
+        "s_or_b32 %[flt], %[flt], 8\n\t"
+        "s_mov_b32 %[st], 0\n\t"
+        "s_mov_b32 %[l], 0\n\t"
+        "s_mov_b32 %[e], 0\n"
+        "L_sexit_%=:\n\t"
+        "s_waitcnt vmcnt(0)\n\t"
+        "s_mov_b64 exec, s[96:97]\n\t"
+        : [i] "+s"(i), [st] "+s"(st), [l] "+s"(l), [e] "+s"(e), [flt] "+s"(flt)
+        : [slots_lo] "s"(slots_lo), [slots_hi] "s"(slots_hi), [lr_lo] "s"(lr_lo),
+          [lr_hi] "s"(lr_hi), [root_lo] "s"(root_lo), [root_hi] "s"(root_hi), [nb] "s"(nb),
+          [m] "s"(m), [vocab] "s"(vocab), [tv] "v"(tv), [lane16] "v"(lane16)
+        : "memory", "vcc", "scc",
+          "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", "s72", "s73", "s74", "s75",
+          "s76", "s77", "s78", "s79", "s96", "s97",
+          "v41", "v42", "v43", "v44", "v45", "v46", "v47");
+}
+
 // Wave 0: feed `count` tokens to the static cursor; stops in front of a token
 // outside the vocabulary (wave 1 reports it).
 __device__ __forceinline__ void static_feed(const StaticView &S, const int32_t *tok, int64_t count,
@@ -944,14 +1066,30 @@ __device__ __forceinline__ void static_feed(const StaticView &S, const int32_t *
                                             uint32_t &e, uint32_t &fault)
 {
     bool stop = false;
+    const bool in_asm = (S.n_buckets >> 32) == 0;
     for (int64_t base = 0; base < count && !stop; base += 64) {
         const int m = (int)((count - base) < 64 ? (count - base) : 64);
         uint32_t tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
         pin_v(tv);
-        for (int i = 0; i < m; i++) {
-            const uint32_t t = lane_get(tv, i);
-            if (t >= vocab) { stop = true; break; }
-            static_transfer(S, t, lane, s, l, e, fault);
+        if (in_asm) {
+            const uint64_t a_sl = (uint64_t)S.slots, a_lr = (uint64_t)S.linkrec,
+                           a_rt = (uint64_t)S.root;
+            uint32_t i = 0, flt = 0;
+            uint32_t a_s = uni(s), a_l = uni(l), a_e = uni(e);
+            static_feed_asm(uni((uint32_t)a_sl), uni((uint32_t)(a_sl >> 32)), uni((uint32_t)a_lr),
+                            uni((uint32_t)(a_lr >> 32)), uni((uint32_t)a_rt),
+                            uni((uint32_t)(a_rt >> 32)), uni((uint32_t)S.n_buckets),
+                            uni((uint32_t)m), uni(vocab), tv, (uint32_t)(lane & 7) * 16u, i, a_s,
+                            a_l, a_e, flt);
+            s = a_s; l = a_l; e = a_e;
+            fault |= flt;
+            if ((int)i < m) stop = true;
+        } else {
+            for (int i = 0; i < m; i++) {
+                const uint32_t t = lane_get(tv, i);
+                if (t >= vocab) { stop = true; break; }
+                static_transfer(S, t, lane, s, l, e, fault);
+            }
         }
     }
 }
