@@ -589,6 +589,18 @@ __device__ __forceinline__ u32x4 table_rsrc(const void *base, uint32_t bytes)
         "s_mov_b32 s73, vcc_lo\n\t"                                                   \
         "s_mov_b32 s74, s70\n\t"
 
+// last's record {n | P << 16, n | none << 16, t, cur} -> table (one lane)
+#define SAM_STORE_LAST                                                                \
+        "s_lshl_b32 s69, s87, 4\n\t"                                                 \
+        "s_mov_b64 exec, 1\n\t"                                                      \
+        "v_mov_b32 v40, s69\n\t"                                                     \
+        "v_mov_b32 v50, s80\n\t"                                                     \
+        "v_mov_b32 v51, s81\n\t"                                                     \
+        "v_mov_b32 v52, s64\n\t"                                                     \
+        "v_mov_b32 v53, s82\n\t"                                                     \
+        "buffer_store_dwordx4 v[50:53], v40, %[rrec], 0 offen\n\t"                   \
+        "s_mov_b64 exec, 0xffff\n\t"
+
 __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_t nb, uint32_t m,
                                                  uint32_t vocab, uint32_t tv, uint32_t lo,
                                                  uint32_t &i, uint32_t &n, uint32_t &ns,
@@ -619,15 +631,8 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_lshl_b32 s80, %[P], 16\n\t"
         "s_or_b32 s80, s80, %[n]\n\t"
         "s_or_b32 s81, %[n], 0xffff0000\n\t"
-        "s_lshl_b32 s69, %[last], 4\n\t"
-        "s_mov_b64 exec, 1\n\t"
-        "v_mov_b32 v40, s69\n\t"
-        "v_mov_b32 v50, s80\n\t"
-        "v_mov_b32 v51, s81\n\t"
-        "v_mov_b32 v52, s64\n\t"
-        "v_mov_b32 v53, s82\n\t"
-        "buffer_store_dwordx4 v[50:53], v40, %[rrec], 0 offen\n\t"
-        "s_mov_b64 exec, 0xffff\n\t"
+        // (stored once the loads this token waits for are in flight, so that the
+        // wave never waits for the store itself)
         "s_add_u32 %[ns], %[ns], 1\n\t"
         "s_add_u32 %[nt], %[nt], 1\n\t"
         "s_add_u32 %[n], %[n], 1\n\t"
@@ -720,7 +725,7 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_lshr_b32 s69, %[r0], 16\n\t"
         "s_mov_b32 s72, -1\n\t"
         "s_cmp_eq_u32 s69, 0xffff\n\t"
-        "s_cbranch_scc1 L_next_%=\n\t"          // P is the root: it stays the cursor
+        "s_cbranch_scc1 L_atroot_%=\n\t"        // P is the root: it stays the cursor
         "s_mov_b32 %[P], s69\n\t"
         SAM_REC_AND_PROBE
         "s_branch L_walk_%=\n"
@@ -735,10 +740,12 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_mul_i32 s71, s65, 0x85ebca77\n\t"
         SAM_HASH("s75", "s68", "s71")
         SAM_LOAD_BUCKET("v[44:45]", "s75")
-        "s_waitcnt vmcnt(1)\n\t"
+        SAM_STORE_LAST
+        "s_waitcnt vmcnt(2)\n\t"
         "s_branch L_qrec_%=\n"
         "L_noprefetch_%=:\n\t"
-        "s_waitcnt vmcnt(0)\n"
+        SAM_STORE_LAST
+        "s_waitcnt vmcnt(1)\n"
         "L_qrec_%=:\n\t"
         "v_readfirstlane_b32 s76, v46\n\t"
         "v_readfirstlane_b32 s77, v47\n\t"
@@ -767,7 +774,7 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_lshl_b32 s85, s68, 17\n\t"
         "s_or_b32 s85, s85, s65\n\t"
         "s_mov_b32 s72, s75\n\t"
-        "s_waitcnt vmcnt(0)\n\t"
+        "s_waitcnt vmcnt(1)\n\t"
         "v_mov_b32 v42, v44\n\t"
         "v_mov_b32 v43, v45\n\t"
         "v_cmp_eq_u32 vcc, s85, v44\n\t"
@@ -907,6 +914,9 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_mov_b32 %[r2], s91\n\t"
         "s_mov_b32 %[r3], s92\n\t"
         "s_mov_b32 s72, -1\n"
+        "s_branch L_next_%=\n"
+        "L_atroot_%=:\n\t"
+        SAM_STORE_LAST
         // ---- next token -------------------------------------------------------------
         "L_next_%=:\n\t"
         "s_mov_b32 %[i], s67\n\t"
@@ -930,6 +940,7 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
           "v52", "v53", "v54");
 }
 #undef SAM_HASH
+#undef SAM_STORE_LAST
 #undef SAM_LOAD_BUCKET
 #undef SAM_NEXT_BUCKET
 #undef SAM_GUARD
