@@ -547,7 +547,7 @@ __device__ __forceinline__ u32x4 table_rsrc(const void *base, uint32_t bytes)
 //   s83 where the transition to q sits (slot index, -2: inline)   s84 slot index
 //   s85 key      s86 loop guard   s87 last before this token   s88 clone
 //   s89..s92 record of the clone  s93 list cursor  s94 token of a copied slot
-//   s95 its target
+//   s95 its target   s98 scratch (slot bit, address)   s99 the next state up the path
 //   v40 v41 addresses   v42:43 probe bucket   v44:45 next token's bucket
 //   v46:49 record load  v50:53 store data  v54 store data of 16-bit fields   s96:97 exec on entry
 // The probe of a bucket: lanes 0..15 load its 16 slots; hit mask = lanes whose
@@ -685,12 +685,25 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_mov_b32 s83, -2\n\t"
         "s_branch L_found_%=\n"
         "L_miss_%=:\n\t"
+        // (P, t) is missing.  The next state up the path is known from P's record, so
+        // its record and its bucket for t are requested first; the stores that give P
+        // its transition follow and are not waited for.
+        "s_add_u32 %[nt], %[nt], 1\n\t"
+        "s_lshr_b32 s99, %[r0], 16\n\t"
+        "s_cmp_eq_u32 s99, 0xffff\n\t"
+        "s_cbranch_scc1 L_ins_%=\n\t"
+        "s_lshl_b32 s70, s99, 4\n\t"
+        "v_mov_b32 v40, s70\n\t"
+        "buffer_load_dwordx4 v[46:49], v40, %[rrec], 0 offen\n\t"
+        SAM_HASH("s75", "s99", "s66")
+        SAM_LOAD_BUCKET("v[44:45]", "s75")
+        "L_ins_%=:\n\t"
         // (P, t) -> cur: inline if P has no transition yet, else into the empty slot
         "s_cmp_eq_u32 %[r2], -1\n\t"
         "s_cbranch_scc1 L_ins_inline_%=\n\t"
-        "s_ff1_i32_b32 s69, s74\n\t"
+        "s_ff1_i32_b32 s98, s74\n\t"
         "s_lshl_b32 s84, s72, 4\n\t"
-        "s_add_u32 s84, s84, s69\n\t"
+        "s_add_u32 s84, s84, s98\n\t"
         "s_lshl_b32 s85, %[P], 17\n\t"
         "s_or_b32 s85, s85, s64\n\t"
         "s_and_b32 s70, %[r1], 0xffff0000\n\t"
@@ -709,7 +722,15 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_and_b32 %[r1], %[r1], 0xffff\n\t"
         "s_lshl_b32 s69, s84, 16\n\t"
         "s_or_b32 %[r1], %[r1], s69\n\t"
-        "s_branch L_inserted_%=\n"
+        "s_cmp_eq_u32 s99, 0xffff\n\t"
+        "s_cbranch_scc1 L_atroot_%=\n\t"        // P is the root: it stays the cursor
+        // the slot just taken still reads as empty in a bucket fetched before the
+        // store: if the next state's bucket is the same one, take it out of the mask
+        "s_lshl_b32 s98, 1, s98\n\t"
+        "s_cmp_eq_u32 s72, s75\n\t"
+        "s_cselect_b32 s98, s98, 0\n\t"
+        "s_waitcnt vmcnt(2)\n\t"
+        "s_branch L_advance_%=\n"
         "L_ins_inline_%=:\n\t"
         "s_lshl_b32 s71, %[P], 4\n\t"
         "s_mov_b64 exec, 1\n\t"
@@ -719,15 +740,27 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "buffer_store_dwordx2 v[50:51], v41, %[rrec], 0 offen offset:8\n\t"
         "s_mov_b64 exec, 0xffff\n\t"
         "s_mov_b32 %[r2], s64\n\t"
-        "s_mov_b32 %[r3], s82\n"
-        "L_inserted_%=:\n\t"
-        "s_add_u32 %[nt], %[nt], 1\n\t"
-        "s_lshr_b32 s69, %[r0], 16\n\t"
-        "s_mov_b32 s72, -1\n\t"
-        "s_cmp_eq_u32 s69, 0xffff\n\t"
-        "s_cbranch_scc1 L_atroot_%=\n\t"        // P is the root: it stays the cursor
-        "s_mov_b32 %[P], s69\n\t"
-        SAM_REC_AND_PROBE
+        "s_mov_b32 %[r3], s82\n\t"
+        "s_cmp_eq_u32 s99, 0xffff\n\t"
+        "s_cbranch_scc1 L_atroot_%=\n\t"
+        "s_mov_b32 s98, 0\n\t"
+        "s_waitcnt vmcnt(1)\n"
+        "L_advance_%=:\n\t"
+        // one state up: its record and the reduced bucket become the current ones
+        "s_mov_b32 %[P], s99\n\t"
+        "s_lshl_b32 s85, s99, 17\n\t"
+        "s_or_b32 s85, s85, s64\n\t"
+        "v_cmp_eq_u32 vcc, s85, v44\n\t"
+        "v_cmp_eq_u32 s[70:71], -1, v44\n\t"
+        "v_readfirstlane_b32 %[r0], v46\n\t"
+        "v_readfirstlane_b32 %[r1], v47\n\t"
+        "v_readfirstlane_b32 %[r2], v48\n\t"
+        "v_readfirstlane_b32 %[r3], v49\n\t"
+        "v_mov_b32 v42, v44\n\t"
+        "v_mov_b32 v43, v45\n\t"
+        "s_mov_b32 s73, vcc_lo\n\t"
+        "s_andn2_b32 s74, s70, s98\n\t"
+        "s_mov_b32 s72, s75\n\t"
         "s_branch L_walk_%=\n"
         // ---- q = next(P)[t] exists -----------------------------------------------
         "L_found_%=:\n\t"
@@ -853,12 +886,26 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_mov_b64 exec, 0xffff\n"
         // states further up the path that still lead to q now lead to the clone
         "L_redirect_%=:\n\t"
+        "s_lshr_b32 s99, %[r0], 16\n\t"
+        "s_lshl_b32 s98, %[P], 4\n\t"           // where the store below goes, if inline
+        "s_cmp_eq_u32 s99, 0xffff\n\t"
+        "s_cbranch_scc1 L_red_store_%=\n\t"
+        SAM_GUARD("L_corrupt_%=")
+        // the next state's record and bucket first, then the store (not waited for)
+        "s_mov_b32 %[P], s99\n\t"
+        "s_lshl_b32 s70, %[P], 4\n\t"
+        "v_mov_b32 v40, s70\n\t"
+        "buffer_load_dwordx4 v[46:49], v40, %[rrec], 0 offen\n\t"
+        SAM_HASH("s72", "%[P]", "s66")
+        SAM_LOAD_BUCKET("v[42:43]", "s72")
+        "s_lshl_b32 s85, %[P], 17\n\t"
+        "s_or_b32 s85, s85, s64\n"
+        "L_red_store_%=:\n\t"
         "s_mov_b64 exec, 1\n\t"
         "v_mov_b32 v54, s88\n\t"
         "s_cmp_eq_u32 s83, -2\n\t"
         "s_cbranch_scc0 L_red_slot_%=\n\t"
-        "s_lshl_b32 s69, %[P], 4\n\t"
-        "v_mov_b32 v40, s69\n\t"
+        "v_mov_b32 v40, s98\n\t"
         "buffer_store_short v54, v40, %[rrec], 0 offen offset:12\n\t"
         "s_branch L_red_up_%=\n"
         "L_red_slot_%=:\n\t"
@@ -867,12 +914,17 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "buffer_store_short v54, v40, %[rslt], 0 offen offset:4\n"
         "L_red_up_%=:\n\t"
         "s_mov_b64 exec, 0xffff\n\t"
-        "s_lshr_b32 s69, %[r0], 16\n\t"
-        "s_cmp_eq_u32 s69, 0xffff\n\t"
+        "s_cmp_eq_u32 s99, 0xffff\n\t"
         "s_cbranch_scc1 L_redirected_%=\n\t"
-        SAM_GUARD("L_corrupt_%=")
-        "s_mov_b32 %[P], s69\n\t"
-        SAM_REC_AND_PROBE
+        "s_waitcnt vmcnt(1)\n\t"
+        "v_cmp_eq_u32 vcc, s85, v42\n\t"
+        "v_cmp_eq_u32 s[70:71], -1, v42\n\t"
+        "v_readfirstlane_b32 %[r0], v46\n\t"
+        "v_readfirstlane_b32 %[r1], v47\n\t"
+        "v_readfirstlane_b32 %[r2], v48\n\t"
+        "v_readfirstlane_b32 %[r3], v49\n\t"
+        "s_mov_b32 s73, vcc_lo\n\t"
+        "s_mov_b32 s74, s70\n\t"
         "s_cmp_eq_u32 %[r2], s64\n\t"
         "s_cbranch_scc0 L_red_resolve_%=\n\t"
         "s_cmp_eq_u32 %[r3], s68\n\t"
@@ -916,6 +968,7 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_mov_b32 s72, -1\n"
         "s_branch L_next_%=\n"
         "L_atroot_%=:\n\t"
+        "s_mov_b32 s72, -1\n\t"
         SAM_STORE_LAST
         // ---- next token -------------------------------------------------------------
         "L_next_%=:\n\t"
@@ -935,7 +988,7 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         : "memory", "vcc", "scc",
           "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", "s72", "s73", "s74", "s75",
           "s76", "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87",
-          "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", "s96", "s97",
+          "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", "s96", "s97", "s98", "s99",
           "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", "v50", "v51",
           "v52", "v53", "v54");
 }
