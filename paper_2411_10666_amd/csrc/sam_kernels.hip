@@ -547,7 +547,7 @@ __device__ __forceinline__ u32x4 table_rsrc(const void *base, uint32_t bytes)
 //   s83 where the transition to q sits (slot index, -2: inline)   s84 slot index
 //   s85 key      s86 loop guard   s87 last before this token   s88 clone
 //   s89..s92 record of the clone  s93 list cursor  s94 token of a copied slot
-//   s95 its target   s98 scratch (slot bit, address)   s99 the next state up the path
+//   s95 its target   s100 key of a requested, not yet reduced bucket (-1: none)   s98 scratch (slot bit, address)   s99 the next state up the path
 //   v40 v41 addresses   v42:43 probe bucket   v44:45 next token's bucket
 //   v46:49 record load  v50:53 store data  v54 store data of 16-bit fields   s96:97 exec on entry
 // The probe of a bucket: lanes 0..15 load its 16 slots; hit mask = lanes whose
@@ -570,25 +570,6 @@ __device__ __forceinline__ u32x4 table_rsrc(const void *base, uint32_t bytes)
 #define SAM_GUARD(label)                                                              \
         "s_sub_u32 s86, s86, 1\n\t"                                                   \
         "s_cbranch_scc1 " label "\n\t"
-// record of P and home bucket of (P, t) in one round trip -> r0..r3, s72..s74
-#define SAM_REC_AND_PROBE                                                             \
-        "s_lshl_b32 s70, %[P], 4\n\t"                                                 \
-        "v_mov_b32 v40, s70\n\t"                                                      \
-        "buffer_load_dwordx4 v[46:49], v40, %[rrec], 0 offen\n\t"                     \
-        SAM_HASH("s72", "%[P]", "s66")                                                \
-        SAM_LOAD_BUCKET("v[42:43]", "s72")                                            \
-        "s_lshl_b32 s85, %[P], 17\n\t"                                                \
-        "s_or_b32 s85, s85, s64\n\t"                                                  \
-        "s_waitcnt vmcnt(0)\n\t"                                                      \
-        "v_cmp_eq_u32 vcc, s85, v42\n\t"                                              \
-        "v_cmp_eq_u32 s[70:71], -1, v42\n\t"                                          \
-        "v_readfirstlane_b32 %[r0], v46\n\t"                                          \
-        "v_readfirstlane_b32 %[r1], v47\n\t"                                          \
-        "v_readfirstlane_b32 %[r2], v48\n\t"                                          \
-        "v_readfirstlane_b32 %[r3], v49\n\t"                                          \
-        "s_mov_b32 s73, vcc_lo\n\t"                                                   \
-        "s_mov_b32 s74, s70\n\t"
-
 // last's record {n | P << 16, n | none << 16, t, cur} -> table (one lane)
 #define SAM_STORE_LAST                                                                \
         "s_lshl_b32 s69, s87, 4\n\t"                                                 \
@@ -611,6 +592,7 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
     asm volatile(
         "s_mov_b64 s[96:97], exec\n\t"
         "s_mov_b64 exec, 0xffff\n\t"
+        "s_mov_b32 s100, -1\n\t"
         "s_mov_b32 s72, -1\n"
         // ---- one token ---------------------------------------------------------
         "L_token_%=:\n\t"
@@ -645,7 +627,20 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_cmp_eq_u32 %[r2], s64\n\t"
         "s_cbranch_scc1 L_inline_%=\n\t"
         "s_cmp_eq_u32 s72, -1\n\t"
-        "s_cbranch_scc0 L_resolve_%=\n\t"
+        "s_cbranch_scc1 L_probe_%=\n\t"
+        "s_cmp_eq_u32 s100, -1\n\t"
+        "s_cbranch_scc1 L_resolve_%=\n\t"
+        // the bucket was requested at the end of the last token and not looked at yet
+        "s_waitcnt vmcnt(0)\n\t"
+        "v_mov_b32 v42, v44\n\t"
+        "v_mov_b32 v43, v45\n\t"
+        "v_cmp_eq_u32 vcc, s100, v44\n\t"
+        "v_cmp_eq_u32 s[70:71], -1, v44\n\t"
+        "s_mov_b32 s100, -1\n\t"
+        "s_mov_b32 s73, vcc_lo\n\t"
+        "s_mov_b32 s74, s70\n\t"
+        "s_branch L_resolve_%=\n"
+        "L_probe_%=:\n\t"
         // no probe held for (P, t): fetch and reduce its home bucket
         SAM_HASH("s72", "%[P]", "s66")
         SAM_LOAD_BUCKET("v[42:43]", "s72")
@@ -683,6 +678,7 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "L_inline_%=:\n\t"
         "s_mov_b32 s68, %[r3]\n\t"
         "s_mov_b32 s83, -2\n\t"
+        "s_mov_b32 s100, -1\n\t"               // a bucket still on the way is not needed
         "s_branch L_found_%=\n"
         "L_miss_%=:\n\t"
         // (P, t) is missing.  The next state up the path is known from P's record, so
@@ -883,7 +879,14 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "v_mov_b32 v52, s91\n\t"
         "v_mov_b32 v53, s92\n\t"
         "buffer_store_dwordx4 v[50:53], v40, %[rrec], 0 offen\n\t"
-        "s_mov_b64 exec, 0xffff\n"
+        "s_mov_b64 exec, 0xffff\n\t"
+        // the next token starts at the clone: request its bucket there now that the
+        // clone's transitions are all stored (a request before them could miss one)
+        "s_cmp_eq_u32 s65, -1\n\t"
+        "s_cbranch_scc1 L_redirect_%=\n\t"
+        "s_mul_i32 s71, s65, 0x85ebca77\n\t"
+        SAM_HASH("s75", "s88", "s71")
+        SAM_LOAD_BUCKET("v[44:45]", "s75")
         // states further up the path that still lead to q now lead to the clone
         "L_redirect_%=:\n\t"
         "s_lshr_b32 s99, %[r0], 16\n\t"
@@ -965,7 +968,14 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_mov_b32 %[r1], s90\n\t"
         "s_mov_b32 %[r2], s91\n\t"
         "s_mov_b32 %[r3], s92\n\t"
-        "s_mov_b32 s72, -1\n"
+        "s_mov_b32 s72, -1\n\t"
+        "s_cmp_eq_u32 s65, -1\n\t"
+        "s_cbranch_scc1 L_next_%=\n\t"
+        // its bucket is on the way; it is waited for and reduced only if the next
+        // token does not take the clone's inline transition
+        "s_lshl_b32 s100, s88, 17\n\t"
+        "s_or_b32 s100, s100, s65\n\t"
+        "s_mov_b32 s72, s75\n\t"
         "s_branch L_next_%=\n"
         "L_atroot_%=:\n\t"
         "s_mov_b32 s72, -1\n\t"
@@ -989,7 +999,7 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
           "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", "s72", "s73", "s74", "s75",
           "s76", "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87",
           "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", "s96", "s97", "s98", "s99",
-          "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", "v50", "v51",
+          "s100", "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", "v50", "v51",
           "v52", "v53", "v54");
 }
 #undef SAM_HASH
@@ -997,7 +1007,6 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
 #undef SAM_LOAD_BUCKET
 #undef SAM_NEXT_BUCKET
 #undef SAM_GUARD
-#undef SAM_REC_AND_PROBE
 
 // ---- per-wave work shared by the step, ingest and replay kernels -------------
 
