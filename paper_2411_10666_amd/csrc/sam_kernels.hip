@@ -540,14 +540,14 @@ __device__ __forceinline__ u32x4 table_rsrc(const void *base, uint32_t bytes)
 // r0..r3 are the record of P as stored in the table.
 //
 // Register use inside (all named registers are scratch for this block):
-//   s64 t        s65 next token (-1: none)   s66 t * c2      s67 i + 1
+//   s64 t        s65 next token (-1: none)   s66 t * c2
 //   s68 q        s69..s71 scratch            s72 probe bucket (-1: no probe held)
 //   s73 probe hit mask   s74 probe empty mask   s75 bucket of (q, next token)
 //   s76..s79 record of q        s80 s81 words 0, 1 of last's record   s82 cur
 //   s83 where the transition to q sits (slot index, -2: inline)   s84 slot index
 //   s85 key      s86 loop guard   s87 last before this token   s88 clone
 //   s89..s92 record of the clone  s93 list cursor  s94 token of a copied slot
-//   s95 its target   s100 key of a requested, not yet reduced bucket (-1: none)   s98 scratch (slot bit, address)   s99 the next state up the path
+//   s95 its target   s67 key of a requested, not yet reduced bucket (-1: none)   s98 scratch (slot bit, address)   s99 the next state up the path
 //   v40 v41 addresses   v42:43 probe bucket   v44:45 next token's bucket
 //   v46:49 record load  v50:53 store data  v54 store data of 16-bit fields   s96:97 exec on entry
 // The probe of a bucket: lanes 0..15 load its 16 slots; hit mask = lanes whose
@@ -592,19 +592,19 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
     asm volatile(
         "s_mov_b64 s[96:97], exec\n\t"
         "s_mov_b64 exec, 0xffff\n\t"
-        "s_mov_b32 s100, -1\n\t"
+        "s_mov_b32 s67, -1\n\t"
         "s_mov_b32 s72, -1\n"
         // ---- one token ---------------------------------------------------------
         "L_token_%=:\n\t"
         "v_readlane_b32 s64, %[tv], %[i]\n\t"
-        "s_add_u32 s67, %[i], 1\n\t"
+        "s_add_u32 s69, %[i], 1\n\t"
         "s_mov_b32 s65, -1\n\t"
         "s_cmp_ge_u32 s64, %[vocab]\n\t"
         "s_cbranch_scc1 L_exit_%=\n\t"
         "s_mul_i32 s66, s64, 0x85ebca77\n\t"
-        "s_cmp_lt_u32 s67, %[m]\n\t"
+        "s_cmp_lt_u32 s69, %[m]\n\t"
         "s_cbranch_scc0 L_notn_%=\n\t"
-        "v_readlane_b32 s65, %[tv], s67\n\t"
+        "v_readlane_b32 s65, %[tv], s69\n\t"
         "s_cmp_lt_u32 s65, %[vocab]\n\t"
         "s_cselect_b32 s65, s65, -1\n"
         "L_notn_%=:\n\t"
@@ -628,15 +628,15 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_cbranch_scc1 L_inline_%=\n\t"
         "s_cmp_eq_u32 s72, -1\n\t"
         "s_cbranch_scc1 L_probe_%=\n\t"
-        "s_cmp_eq_u32 s100, -1\n\t"
+        "s_cmp_eq_u32 s67, -1\n\t"
         "s_cbranch_scc1 L_resolve_%=\n\t"
         // the bucket was requested at the end of the last token and not looked at yet
         "s_waitcnt vmcnt(0)\n\t"
         "v_mov_b32 v42, v44\n\t"
         "v_mov_b32 v43, v45\n\t"
-        "v_cmp_eq_u32 vcc, s100, v44\n\t"
+        "v_cmp_eq_u32 vcc, s67, v44\n\t"
         "v_cmp_eq_u32 s[70:71], -1, v44\n\t"
-        "s_mov_b32 s100, -1\n\t"
+        "s_mov_b32 s67, -1\n\t"
         "s_mov_b32 s73, vcc_lo\n\t"
         "s_mov_b32 s74, s70\n\t"
         "s_branch L_resolve_%=\n"
@@ -678,7 +678,7 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "L_inline_%=:\n\t"
         "s_mov_b32 s68, %[r3]\n\t"
         "s_mov_b32 s83, -2\n\t"
-        "s_mov_b32 s100, -1\n\t"               // a bucket still on the way is not needed
+        "s_mov_b32 s67, -1\n\t"               // a bucket still on the way is not needed
         "s_branch L_found_%=\n"
         "L_miss_%=:\n\t"
         // (P, t) is missing.  The next state up the path is known from P's record, so
@@ -973,8 +973,8 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_cbranch_scc1 L_next_%=\n\t"
         // its bucket is on the way; it is waited for and reduced only if the next
         // token does not take the clone's inline transition
-        "s_lshl_b32 s100, s88, 17\n\t"
-        "s_or_b32 s100, s100, s65\n\t"
+        "s_lshl_b32 s67, s88, 17\n\t"
+        "s_or_b32 s67, s67, s65\n\t"
         "s_mov_b32 s72, s75\n\t"
         "s_branch L_next_%=\n"
         "L_atroot_%=:\n\t"
@@ -982,7 +982,7 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         SAM_STORE_LAST
         // ---- next token -------------------------------------------------------------
         "L_next_%=:\n\t"
-        "s_mov_b32 %[i], s67\n\t"
+        "s_add_u32 %[i], %[i], 1\n\t"
         "s_cmp_lt_u32 %[i], %[m]\n\t"
         "s_cbranch_scc1 L_token_%=\n\t"
         "s_branch L_exit_%=\n"
@@ -999,7 +999,7 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
           "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", "s72", "s73", "s74", "s75",
           "s76", "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87",
           "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95", "s96", "s97", "s98", "s99",
-          "s100", "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", "v50", "v51",
+          "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47", "v48", "v49", "v50", "v51",
           "v52", "v53", "v54");
 }
 #undef SAM_HASH
@@ -1136,13 +1136,16 @@ __device__ __forceinline__ void static_feed_asm(uint32_t slots_lo, uint32_t slot
 // outside the vocabulary (wave 1 reports it).
 __device__ __forceinline__ void static_feed(const StaticView &S, const int32_t *tok, int64_t count,
                                             uint32_t vocab, int lane, uint32_t &s, uint32_t &l,
-                                            uint32_t &e, uint32_t &fault)
+                                            uint32_t &e, uint32_t &fault, bool have_first = false,
+                                            uint32_t first = 0)
 {
     bool stop = false;
     const bool in_asm = (S.n_buckets >> 32) == 0;
     for (int64_t base = 0; base < count && !stop; base += 64) {
         const int m = (int)((count - base) < 64 ? (count - base) : 64);
-        uint32_t tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
+        uint32_t tv;
+        if (have_first && base == 0) tv = first;     // fetched by the caller with its other loads
+        else tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
         pin_v(tv);
         if (in_asm) {
             const uint64_t a_sl = (uint64_t)S.slots, a_lr = (uint64_t)S.linkrec,
@@ -1171,12 +1174,15 @@ __device__ __forceinline__ void static_feed(const StaticView &S, const int32_t *
 template <class L>
 __device__ __forceinline__ void dyn_feed(const DynSeq &D, const int32_t *tok, int64_t count,
                                          uint32_t vocab, int lane, DynCursor<L> &c,
-                                         uint32_t &fault)
+                                         uint32_t &fault, bool have_first = false,
+                                         uint32_t first = 0)
 {
     bool stop = false;
     for (int64_t base = 0; base < count && !stop; base += 64) {
         const int m = (int)((count - base) < 64 ? (count - base) : 64);
-        uint32_t tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
+        uint32_t tv;
+        if (have_first && base == 0) tv = first;     // fetched by the caller with its other loads
+        else tv = lane < m ? (uint32_t)tok[base + lane] : 0u;
         pin_v(tv);
         c.pf_ok = false;
         const uint32_t n_chunk = c.n;
@@ -1260,6 +1266,22 @@ __device__ __forceinline__ void load_cursor(const SeqMeta *meta, DynCursor<L> &c
     c.pf.sl = typename L::RawSlot();
 }
 
+// The same from the 16 words of the block held one per lane (lane i = word i).
+template <class L>
+__device__ __forceinline__ void cursor_from_lanes(uint32_t mv, DynCursor<L> &c)
+{
+    c.n = lane_get(mv, 3); c.n_states = lane_get(mv, 4); c.last = lane_get(mv, 5);
+    c.n_trans = lane_get(mv, 6);
+    c.P = lane_get(mv, 8);
+    c.RP.len = lane_get(mv, 9); c.RP.link = lane_get(mv, 10);
+    c.RP.endpos = lane_get(mv, 11); c.RP.head = lane_get(mv, 12);
+    c.RP.itok = lane_get(mv, 13); c.RP.idst = lane_get(mv, 14);
+    c.rec_bytes = 0;
+    c.pf_ok = false;
+    c.pf.b = 0; c.pf.mh = 0; c.pf.me = 0;
+    c.pf.sl = typename L::RawSlot();
+}
+
 // all of the dynamic cursor except meta->n (see the kernels for why)
 template <class L>
 __device__ __forceinline__ void store_cursor(SeqMeta *meta, const DynCursor<L> &c)
@@ -1321,36 +1343,54 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
 
+    // Kernel arguments span three cache lines; named together here, they are all
+    // requested before the first of them is waited for.
+    {
+        const uint32_t a0 = (uint32_t)(uintptr_t)S.slots, a1 = (uint32_t)(uintptr_t)B.meta,
+                       a2 = (uint32_t)(uintptr_t)B.dyn_slots, a3 = (uint32_t)(uintptr_t)tokens,
+                       a4 = (uint32_t)(uintptr_t)source;
+        asm volatile("" :: "s"(a0), "s"(a1), "s"(a2), "s"(a3), "s"(a4));
+    }
     SeqMeta *meta = &B.meta[b];
-    const uint32_t n0 = uni(meta->n);
 
-    // which tokens
+    // A step's first round trip fetches everything it needs before its first token
+    // at once: the cursor block (16 words, one per lane), the count and the row of
+    // accepted tokens.  Read one after the other they cost a launch three to five
+    // dependent misses, which is a tenth of a whole step.
+    static_assert(sizeof(SeqMeta) == 64, "the cursor block is read as 16 words");
+    uint32_t mv = reinterpret_cast<const uint32_t *>(meta)[lane & 15];
     const int32_t *tok;
     int64_t count;
     uint32_t fault = 0;
+    uint32_t first = 0;
     if (kIngest) {
         const int64_t o0 = offsets[blockIdx.x], o1 = offsets[blockIdx.x + 1];
         tok = tokens + o0;
         count = o1 - o0;
     } else {
         tok = tokens + (int64_t)b * B.max_accept;
-        count = counts[b];
+        uint32_t raw = (uint32_t)counts[b];
+        first = lane < B.max_accept ? (uint32_t)tok[lane] : 0u;   // the row exists whatever the count
+        asm volatile("" : "+v"(mv), "+v"(first), "+s"(raw));      // all three in flight before any is used
+        count = (int32_t)raw;
         if (count < 0 || count > B.max_accept) { fault |= SAM_STATUS_COUNT_BIT; count = 0; }
     }
+    pin_v(mv);
+    const uint32_t n0 = lane_get(mv, 3);
     count = (int64_t)uni((uint32_t)count);
     if ((int64_t)n0 + count > (int64_t)B.max_seq_len) { fault |= SAM_STATUS_CAPACITY_BIT; count = 0; }
     const uint32_t vocab = (uint32_t)B.vocab;
 
     if (wave == 0) {
-        uint32_t s = uni(meta->s1), l = uni(meta->l1), e = uni(meta->e1);
-        if (B.has_static) static_feed(S, tok, count, vocab, lane, s, l, e, fault);
+        uint32_t s = lane_get(mv, 0), l = lane_get(mv, 1), e = lane_get(mv, 2);
+        if (B.has_static) static_feed(S, tok, count, vocab, lane, s, l, e, fault, !kIngest, first);
         if (lane == 0) { sh[0] = s; sh[1] = l; sh[2] = e; sh[6] = fault & SAM_STATUS_INTERNAL_BIT; }
     } else {
         const DynSeq D = dyn_region<L>(B, b);
         DynCursor<L> c;
-        load_cursor<L>(meta, c);
+        cursor_from_lanes<L>(mv, c);
         c.rec_bytes = (uint32_t)B.max_states * 16u;
-        dyn_feed<L>(D, tok, count, vocab, lane, c, fault);
+        dyn_feed<L>(D, tok, count, vocab, lane, c, fault, !kIngest, first);
         if (c.n != n0) flush_last<L>(D, c, lane);
         if (lane == 0) {
             sh[3] = c.P == kNil ? 0u : c.RP.len;
