@@ -290,9 +290,12 @@ int sam_batch_status(const sam_batch *batch, uint32_t *status, void *hip_stream)
 /*
  * Testing aid.  Per-sequence tables come in two layouts: a compact one (16-bit
  * state ids; chosen when max_seq_len <= 16366 and vocab <= 131072) and a wide
- * one (32-bit ids, any size).  mode 1 makes every later sam_batch_init in this
- * process use the wide layout, mode 0 restores the automatic choice.  Results
- * are identical either way.
+ * one (32-bit ids, any size).  Bit 0 of mode makes every later sam_batch_init
+ * in this process use the wide layout; bit 1 makes it size the per-sequence
+ * slot tables as tightly as correctness allows (max_seq_len + 16 slots instead
+ * of twice that), so that nearly full buckets and sweeps into the next bucket,
+ * rare otherwise, happen all the time.  mode 0 restores the defaults.  Results
+ * are identical in every mode.
  */
 int sam_set_layout_override(int mode);
 

@@ -20,7 +20,7 @@ using namespace sam;
 namespace {
 
 thread_local std::string g_err;
-int g_layout_override = 0;   // 0: pick per batch, 1: always the wide layout
+int g_layout_override = 0;   // bit 0: always the wide layout, bit 1: tight slot tables
 HostSam::ProgressFn g_progress = nullptr;
 void *g_progress_user = nullptr;
 
@@ -356,9 +356,12 @@ int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
     v.vocab = vocab;
     v.max_seq_len = (uint32_t)max_seq_len;
     v.max_states = 2u * (uint32_t)max_seq_len + 2u;
-    v.compact = (g_layout_override == 0 && max_seq_len <= kCompactMaxSeqLen &&
+    v.compact = ((g_layout_override & 1) == 0 && max_seq_len <= kCompactMaxSeqLen &&
                  vocab <= kCompactMaxVocab) ? 1 : 0;
-    const uint64_t dyn_slots = dynamic_slots_for(max_seq_len);
+    // a sequence never holds more than max_seq_len - 1 transitions in its slots
+    const uint64_t dyn_slots = (g_layout_override & 2)
+                                   ? ((uint64_t)max_seq_len + 16 + 15) / 16 * 16
+                                   : dynamic_slots_for(max_seq_len);
     const size_t slot_bytes = v.compact ? sizeof(SlotCompact) : sizeof(Slot);
     const size_t rec_bytes = v.compact ? sizeof(DynRecCompact) : sizeof(DynRec);
     v.dyn_buckets = (uint32_t)(dyn_slots * slot_bytes / 128);
@@ -554,7 +557,7 @@ int sam_set_progress_callback(sam_progress_fn fn, void *user)
 
 int sam_set_layout_override(int mode)
 {
-    if (mode != 0 && mode != 1) return fail(SAM_EINVAL, "sam_set_layout_override: mode is 0 or 1");
+    if (mode < 0 || mode > 3) return fail(SAM_EINVAL, "sam_set_layout_override: mode is 0 .. 3");
     g_layout_override = mode;
     return SAM_OK;
 }

@@ -80,6 +80,44 @@ def test_wide_layout_forced(seed, vocab):
     assert_same(g, r)
 
 
+@pytest.mark.parametrize("mode,T", [(2, 300), (3, 300), (2, 3000)])
+@pytest.mark.parametrize("seed,vocab", [(40, 3), (41, 50), (42, 32000)])
+def test_tight_slot_tables(seed, vocab, mode, T):
+    """Slot tables sized to the bare minimum (a testing mode of the library), both
+    layouts, sequences grown to exactly max_seq_len: buckets fill up, lookups and
+    inserts sweep on into the next bucket, and the slot an insert takes is often in
+    the bucket that was fetched ahead for the next state -- paths that the normal
+    sizing makes rare."""
+    from paper_2411_10666_amd import binding as sam
+    B, A, L = 9, 7, 5
+    rng = np.random.default_rng(seed)
+    corpus = rng.integers(0, vocab, size=800).astype(np.int32)
+    prompts = [rng.integers(0, vocab, size=int(rng.integers(0, T // 5))).astype(np.int32)
+               for _ in range(B)]
+    used = np.array([len(p) for p in prompts])
+    rows_c, rows_a = [], []
+    while (used < T).any():
+        c = np.minimum(rng.integers(0, A + 1, size=B), T - used)
+        a = rng.integers(0, vocab, size=(B, A)).astype(np.int32)
+        for b in range(B):                      # now and then repeat what the sequence just said
+            if c[b] >= 2 and rng.random() < 0.3:
+                a[b, 1:] = a[b, 0]
+        rows_c.append(c)
+        rows_a.append(a)
+        used += c
+    counts = np.array(rows_c, dtype=np.int32)
+    acc = np.array(rows_a, dtype=np.int32)
+    _say("tight tables seed=%d vocab=%d mode=%d T=%d steps=%d" % (seed, vocab, mode, T, len(counts)))
+    sam.sam_set_layout_override(mode)
+    try:
+        g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L)
+    finally:
+        sam.sam_set_layout_override(0)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r)
+
+
 def test_wide_layout_chosen_for_large_vocab():
     """A vocabulary above 2^17 does not fit the compact slot key."""
     vocab = 200_000
