@@ -16,6 +16,14 @@
 // next token is issued together with the last read of the current one.
 // Sequence b is always served by workgroup b, so its private tables keep
 // hitting the L2 of the same XCD from launch to launch.
+//
+// The two token loops exist twice: in C++ (static_transfer, dyn_expand: every
+// layout, every size) and, for the compact per-sequence tables and corpora below
+// 2^32 buckets, in gfx950 assembly (static_feed_asm, dyn_feed_compact), which is
+// what the benchmark configurations run.  What a token costs is one wavefront's
+// chain of dependent instructions and memory round trips; the assembly needs
+// under half the instructions of the compiled code and waits only for the loads
+// it is about to use.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
