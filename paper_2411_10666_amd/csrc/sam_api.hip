@@ -77,7 +77,7 @@ static void corpus_release_device(sam_corpus *c)
 static int corpus_upload(sam_corpus *c)
 {
     const HostSam &h = c->host;
-    std::vector<LinkRec> lr;
+    std::vector<LinkPair> lr;
     try {
         h.make_linkrec(lr);
     } catch (const std::bad_alloc &) {
@@ -93,9 +93,22 @@ static int corpus_upload(sam_corpus *c)
     HIP_TRY(hipMalloc(&c->d_root, b_root));
     HIP_TRY(hipMalloc(&c->d_slots, b_slots));
     HIP_TRY(hipMemcpy(c->d_text, h.text.data(), b_text, hipMemcpyHostToDevice));
-    HIP_TRY(hipMemcpy(c->d_linkrec, lr.data(), b_lr, hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(c->d_root, h.root.data(), b_root, hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(c->d_slots, h.slots, b_slots, hipMemcpyHostToDevice));
+    {
+        // link pairs -> 32-byte state records with one transition inline
+        void *d_pairs = nullptr;
+        const size_t b_pairs = (size_t)h.n_states * sizeof(LinkPair);
+        HIP_TRY(hipMalloc(&d_pairs, b_pairs));
+        hipError_t e = hipMemcpy(d_pairs, lr.data(), b_pairs, hipMemcpyHostToDevice);
+        if (e == hipSuccess)
+            e = launch_staterec((const LinkPair *)d_pairs, (const Slot *)c->d_slots,
+                                (LinkRec *)c->d_linkrec, h.n_states,
+                                h.n_buckets * kBucketSlots, nullptr);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        (void)hipFree(d_pairs);
+        if (e != hipSuccess) return fail_hip("sam_build: state records", e);
+    }
     c->view.text = (const int32_t *)c->d_text;
     c->view.linkrec = (const LinkRec *)c->d_linkrec;
     c->view.root = (const RootEnt *)c->d_root;

@@ -424,11 +424,11 @@ uint32_t HostSam::find(uint32_t state, uint32_t token) const
     return at == kNil64 ? kNil : slots[at].dst;
 }
 
-void HostSam::make_linkrec(std::vector<LinkRec> &out) const
+void HostSam::make_linkrec(std::vector<LinkPair> &out) const
 {
     out.resize(n_states);
-    out[0] = LinkRec{0, 0};
-    for (uint32_t s = 1; s < n_states; s++) out[s] = LinkRec{link[s], len[link[s]]};
+    out[0] = LinkPair{0, 0};
+    for (uint32_t s = 1; s < n_states; s++) out[s] = LinkPair{link[s], len[link[s]]};
 }
 
 void HostSam::release_build_only() { head.release(); }

@@ -72,7 +72,7 @@ struct HostSam {
     int build_topk(int k, std::string &err, ProgressFn progress = nullptr, void *user = nullptr);
 
     // {link, length(link)} per state, for the device
-    void make_linkrec(std::vector<LinkRec> &out) const;
+    void make_linkrec(std::vector<LinkPair> &out) const;
 
     void release_build_only();   // drop arrays the device does not need
 };

@@ -87,6 +87,10 @@ __device__ __forceinline__ void static_transfer(const StaticView &S, uint32_t t,
         // fetch the suffix-link record together with the bucket: it is only
         // needed on a miss, but then it is already here
         const LinkRec lr = S.linkrec[s];
+        if (uni(lr.itok) == t) {            // the transition the record repeats
+            s = uni(lr.idst); e = uni(lr.iendpos); l += 1;
+            return;
+        }
         uint64_t b = bucket_of(hash_key(s, t), S.n_buckets);
         uint4 sl = reinterpret_cast<const uint4 *>(S.slots)[b * kBucketSlots + (lane & 7)];
         uint32_t mh = (uint32_t)__ballot(sl.x == s && sl.y == t) & 0xFFu;
@@ -1026,7 +1030,7 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
 //   s64 t   s65 t * c2   s66 link-hop guard   s67 bucket-sweep guard
 //   s68:69 s70:71 addresses / compare results   s72 hash   s73 bucket
 //   s74 hit mask   s75 empty mask   s76:77 compare result   s78 s79 scratch
-//   v41 zero   v42:45 slot {state, token, dst, endpos}   v46:47 link record / root entry
+//   v41 zero   v42:45 slot {state, token, dst, endpos}   s88..s92 state record   v46:47 root entry
 __device__ __forceinline__ void static_feed_asm(uint32_t slots_lo, uint32_t slots_hi,
                                                 uint32_t lr_lo, uint32_t lr_hi, uint32_t root_lo,
                                                 uint32_t root_hi, uint32_t nb, uint32_t m,
@@ -1049,12 +1053,15 @@ __device__ __forceinline__ void static_feed_asm(uint32_t slots_lo, uint32_t slot
         "s_cbranch_scc1 L_scorrupt_%=\n\t"
         "s_cmp_eq_u32 %[st], 0\n\t"
         "s_cbranch_scc1 L_sroot_%=\n\t"
-        // suffix-link record of the state, in flight together with the bucket
-        "s_lshl_b32 s68, %[st], 3\n\t"
-        "s_lshr_b32 s69, %[st], 29\n\t"
+        // the state's record {itok, idst, iendpos, link, lenlink}, in flight together
+        // with the bucket.  It comes through the scalar cache (the table is read-only),
+        // which has its own counter: vector loads return in order, so a record behind
+        // a bucket in the same queue could not arrive before it
+        "s_lshl_b32 s68, %[st], 5\n\t"
+        "s_lshr_b32 s69, %[st], 27\n\t"
         "s_add_u32 s68, s68, %[lr_lo]\n\t"
         "s_addc_u32 s69, s69, %[lr_hi]\n\t"
-        "global_load_dwordx2 v[46:47], v41, s[68:69]\n\t"
+        "s_load_dwordx8 s[88:95], s[68:69], 0x0\n\t"
         "s_mul_i32 s72, %[st], 0x9e3779b1\n\t"
         "s_add_u32 s72, s72, s65\n\t"
         "s_lshr_b32 s79, s72, 15\n\t"
@@ -1066,13 +1073,26 @@ __device__ __forceinline__ void static_feed_asm(uint32_t slots_lo, uint32_t slot
         "s_lshr_b32 s79, s72, 15\n\t"
         "s_xor_b32 s72, s72, s79\n\t"
         "s_mul_hi_u32 s73, s72, %[nb]\n\t"
-        "s_mov_b32 s67, %[nb]\n"
-        "L_sload_%=:\n\t"
+        "s_mov_b32 s67, %[nb]\n\t"
         "s_lshl_b32 s70, s73, 7\n\t"
         "s_lshr_b32 s71, s73, 25\n\t"
         "s_add_u32 s70, s70, %[slots_lo]\n\t"
         "s_addc_u32 s71, s71, %[slots_hi]\n\t"
         "global_load_dwordx4 v[42:45], %[lane16], s[70:71]\n\t"
+        // the record is here before the bucket (often from a line the last token
+        // already brought in): if it repeats the transition asked for, the bucket is
+        // not waited for at all
+        "s_waitcnt lgkmcnt(0)\n\t"
+        "s_cmp_eq_u32 s88, s64\n\t"
+        "s_cbranch_scc1 L_sinline_%=\n\t"
+        "s_branch L_swait_%=\n"
+        "L_sload_%=:\n\t"
+        "s_lshl_b32 s70, s73, 7\n\t"
+        "s_lshr_b32 s71, s73, 25\n\t"
+        "s_add_u32 s70, s70, %[slots_lo]\n\t"
+        "s_addc_u32 s71, s71, %[slots_hi]\n\t"
+        "global_load_dwordx4 v[42:45], %[lane16], s[70:71]\n"
+        "L_swait_%=:\n\t"
         "s_waitcnt vmcnt(0)\n\t"
         "v_cmp_eq_u32 vcc, %[st], v42\n\t"
         "v_cmp_eq_u32 s[76:77], s64, v43\n\t"
@@ -1096,9 +1116,14 @@ __device__ __forceinline__ void static_feed_asm(uint32_t slots_lo, uint32_t slot
         "v_readlane_b32 %[st], v44, s78\n\t"
         "v_readlane_b32 %[e], v45, s78\n\t"
         "s_branch L_sdone_%=\n"
+        "L_sinline_%=:\n\t"
+        "s_add_u32 %[l], %[l], 1\n\t"
+        "s_mov_b32 %[st], s89\n\t"
+        "s_mov_b32 %[e], s90\n\t"
+        "s_branch L_sdone_%=\n"
         "L_smiss_%=:\n\t"
-        "v_readfirstlane_b32 %[st], v46\n\t"    // follow the suffix link
-        "v_readfirstlane_b32 %[l], v47\n\t"
+        "s_mov_b32 %[st], s91\n\t"              // follow the suffix link
+        "s_mov_b32 %[l], s92\n\t"
         "s_branch L_stry_%=\n"
         "L_sroot_%=:\n\t"
         "s_lshl_b32 s68, s64, 3\n\t"
@@ -1136,7 +1161,8 @@ __device__ __forceinline__ void static_feed_asm(uint32_t slots_lo, uint32_t slot
           [m] "s"(m), [vocab] "s"(vocab), [tv] "v"(tv), [lane16] "v"(lane16)
         : "memory", "vcc", "scc",
           "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", "s72", "s73", "s74", "s75",
-          "s76", "s77", "s78", "s79", "s96", "s97",
+          "s76", "s77", "s78", "s79", "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95",
+          "s96", "s97",
           "v41", "v42", "v43", "v44", "v45", "v46", "v47");
 }
 
@@ -1554,7 +1580,50 @@ __global__ void sam_debug_kernel(BatchView B, int32_t *s1, int32_t *l1, int32_t 
     if (n_trans) n_trans[b] = (int32_t)m.n_trans;
 }
 
+// ---- the static state records, built once per corpus ------------------------
+
+__global__ void sam_staterec_init_kernel(const LinkPair *pairs, LinkRec *rec, uint32_t n_states)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t s = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; s < n_states; s += stride) {
+        LinkRec r;
+        r.itok = kNil; r.idst = kNil; r.iendpos = 0;
+        r.link = pairs[s].link; r.lenlink = pairs[s].lenlink;
+        r.pad[0] = r.pad[1] = r.pad[2] = 0;
+        rec[s] = r;
+    }
+}
+
+// pass 0: idst = the nearest target created after the state; pass 1: its token
+// and end position (a state has one transition per target at most)
+__global__ void sam_staterec_pick_kernel(const Slot *slots, LinkRec *rec, uint64_t n_slots, int pass)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_slots; i += stride) {
+        const Slot sl = slots[i];
+        if (sl.state == kNil || sl.dst <= sl.state) continue;
+        if (pass == 0) {
+            atomicMin(&rec[sl.state].idst, sl.dst);
+        } else if (rec[sl.state].idst == sl.dst) {
+            rec[sl.state].itok = sl.token;
+            rec[sl.state].iendpos = sl.w;
+        }
+    }
+}
+
 // ---- launchers (called from the C ABI) ------------------------------------
+
+hipError_t launch_staterec(const LinkPair *pairs, const Slot *slots, LinkRec *linkrec,
+                           uint32_t n_states, uint64_t n_slots, hipStream_t stream)
+{
+    hipLaunchKernelGGL(sam_staterec_init_kernel, dim3(4096), dim3(256), 0, stream, pairs, linkrec,
+                       n_states);
+    hipLaunchKernelGGL(sam_staterec_pick_kernel, dim3(8192), dim3(256), 0, stream, slots, linkrec,
+                       n_slots, 0);
+    hipLaunchKernelGGL(sam_staterec_pick_kernel, dim3(8192), dim3(256), 0, stream, slots, linkrec,
+                       n_slots, 1);
+    return hipGetLastError();
+}
 
 hipError_t launch_feed(const StaticView &S, const BatchView &B, const int32_t *seq_map,
                        int n_seqs, const int32_t *tokens, const int64_t *offsets,

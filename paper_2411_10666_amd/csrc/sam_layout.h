@@ -5,7 +5,7 @@
 //
 //  static automaton (read-only on the device)
 //    text[n]                 int32 corpus
-//    linkrec[n_states]       {link, length(link)}                       8 B
+//    linkrec[n_states]       {one transition inline, link, length(link)} 32 B
 //    root[vocab]             {target, min_endpos(target)}, target 0 = none  8 B
 //    slots[n_buckets * 8]    {state, token, target, min_endpos(target)} 16 B
 //                            open addressing, 128-byte buckets of 8 slots,
@@ -45,9 +45,25 @@ struct Slot {            // 16 B
     uint32_t w;          // static: min_endpos(dst); dynamic and host build: next slot of `state`
 };
 
-struct LinkRec {         // 8 B, static automaton
+struct LinkPair {        // 8 B: what the host hands over per state
     uint32_t link;
-    uint32_t lenlink;
+    uint32_t lenlink;    // len(link)
+};
+
+// 32 B per state of the static automaton, built on the device from the link
+// pairs and the slot table.  Besides the suffix link it repeats ONE of the
+// state's transitions: the one to the nearest state created after it.  For a
+// state that stands for a prefix of the corpus this is the transition to the
+// next prefix, whose record is the next or next-but-one in this array -- so
+// while a sequence follows a stretch of the corpus, its lookups read
+// consecutive records (four to a cache line) instead of one random bucket each.
+struct LinkRec {
+    uint32_t itok;       // token of the repeated transition, kNil = none
+    uint32_t idst;       // its target
+    uint32_t iendpos;    // min_endpos(target)
+    uint32_t link;       // link(s) (0 for the root and for states of length 1)
+    uint32_t lenlink;    // len(link(s))
+    uint32_t pad[3];
 };
 
 struct RootEnt {         // 8 B, static automaton; dst == 0 means no transition
