@@ -294,8 +294,9 @@ int sam_batch_status(const sam_batch *batch, uint32_t *status, void *hip_stream)
  * in this process use the wide layout; bit 1 makes it size the per-sequence
  * slot tables as tightly as correctness allows (max_seq_len + 16 slots instead
  * of twice that), so that nearly full buckets and sweeps into the next bucket,
- * rare otherwise, happen all the time.  mode 0 restores the defaults.  Results
- * are identical in every mode.
+ * rare otherwise, happen all the time; bit 2 makes its kernels run the C++ form
+ * of the two token loops instead of the assembly one.  mode 0 restores the
+ * defaults.  Results are identical in every mode.
  */
 int sam_set_layout_override(int mode);
 

@@ -20,7 +20,8 @@ using namespace sam;
 namespace {
 
 thread_local std::string g_err;
-int g_layout_override = 0;   // bit 0: always the wide layout, bit 1: tight slot tables
+int g_layout_override = 0;   // bit 0: always the wide layout, bit 1: tight slot tables,
+                             // bit 2: C++ token loops
 HostSam::ProgressFn g_progress = nullptr;
 void *g_progress_user = nullptr;
 
@@ -382,6 +383,7 @@ int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
     v.draft_len = draft_len;
     v.l_bias = l_bias;
     v.l_threshold = -1;
+    v.no_asm = (g_layout_override & 4) ? 1 : 0;
     v.has_static = corpus ? 1 : 0;
     const size_t b_text = (size_t)batch * max_seq_len * sizeof(int32_t);
     const size_t b_rec = (size_t)batch * v.max_states * rec_bytes;
@@ -570,7 +572,7 @@ int sam_set_progress_callback(sam_progress_fn fn, void *user)
 
 int sam_set_layout_override(int mode)
 {
-    if (mode < 0 || mode > 3) return fail(SAM_EINVAL, "sam_set_layout_override: mode is 0 .. 3");
+    if (mode < 0 || mode > 7) return fail(SAM_EINVAL, "sam_set_layout_override: mode is 0 .. 7");
     g_layout_override = mode;
     return SAM_OK;
 }

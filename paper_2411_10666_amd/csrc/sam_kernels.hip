@@ -20,7 +20,8 @@
 // The two token loops exist twice: in C++ (static_transfer, dyn_expand: every
 // layout, every size) and, for the compact per-sequence tables and corpora below
 // 2^32 buckets, in gfx950 assembly (static_feed_asm, dyn_feed_compact), which is
-// what the benchmark configurations run.  What a token costs is one wavefront's
+// what the benchmark configurations run (template parameter kAsm of the kernels,
+// chosen at launch).  What a token costs is one wavefront's
 // chain of dependent instructions and memory round trips; the assembly needs
 // under half the instructions of the compiled code and waits only for the loads
 // it is about to use.
@@ -528,8 +529,9 @@ __device__ __forceinline__ void flush_last(const DynSeq &D, const DynCursor<L> &
 // hand: one wavefront's dependent instruction chain is what a token costs, and
 // this form needs about half the instructions of the compiled one (records stay
 // packed as stored, no copies between paths, stores under a one-lane exec mask
-// without a branch).  The wide layout and a sequence's very first token take the
-// C++ path.  Every table access goes through a buffer resource whose size is
+// without a branch).  The wide layout takes the C++ path; the kernels are
+// instantiated with one form or the other, never both, because the mere presence
+// of the C++ loop costs the assembly one 2 % (registers, code size).  Every table access goes through a buffer resource whose size is
 // the table's, so an index outside a table reads zeros or is dropped instead of
 // touching foreign memory, and every loop that follows table contents counts
 // down a guard.
@@ -546,8 +548,7 @@ __device__ __forceinline__ u32x4 table_rsrc(const void *base, uint32_t bytes)
     return r;
 }
 
-// Append tokens tv[i .. m) to a sequence whose cursor is not at its very first
-// token (P is a state).  i: index of the next token (in/out); on return i == m,
+// Append tokens tv[i .. m) to a sequence (P = -1: it is still empty).  i: index of the next token (in/out); on return i == m,
 // or tv[i] is outside the vocabulary, or `flt` carries the internal-error bit.
 // r0..r3 are the record of P as stored in the table.
 //
@@ -632,7 +633,17 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_add_u32 %[n], %[n], 1\n\t"
         "s_mov_b32 s87, %[last]\n\t"
         "s_mov_b32 %[last], s82\n\t"
-        "s_add_u32 s86, %[ns], 4\n"
+        "s_add_u32 s86, %[ns], 4\n\t"
+        "s_cmp_eq_u32 %[P], -1\n\t"
+        "s_cbranch_scc0 L_walk_%=\n\t"
+        // the sequence's very first token: last is the root, which now has (t -> cur)
+        // as its inline transition; the cursor is the root
+        "s_mov_b32 %[P], 0\n\t"
+        "s_mov_b32 %[r0], 0xffff0000\n\t"
+        "s_mov_b32 %[r1], 0xffff0000\n\t"
+        "s_mov_b32 %[r2], s64\n\t"
+        "s_mov_b32 %[r3], s82\n\t"
+        "s_branch L_atroot_%=\n"
         // ---- walk last's suffix path: states without a t-transition get one ----
         "L_walk_%=:\n\t"
         SAM_GUARD("L_corrupt_%=")
@@ -1170,11 +1181,11 @@ __device__ __forceinline__ void static_feed_asm(uint32_t slots_lo, uint32_t slot
 // outside the vocabulary (wave 1 reports it).
 __device__ __forceinline__ void static_feed(const StaticView &S, const int32_t *tok, int64_t count,
                                             uint32_t vocab, int lane, uint32_t &s, uint32_t &l,
-                                            uint32_t &e, uint32_t &fault, bool have_first = false,
-                                            uint32_t first = 0)
+                                            uint32_t &e, uint32_t &fault, bool use_asm,
+                                            bool have_first = false, uint32_t first = 0)
 {
     bool stop = false;
-    const bool in_asm = (S.n_buckets >> 32) == 0;
+    const bool in_asm = use_asm;          // the launcher sends corpora beyond 2^32 buckets to C++
     for (int64_t base = 0; base < count && !stop; base += 64) {
         const int m = (int)((count - base) < 64 ? (count - base) : 64);
         uint32_t tv;
@@ -1208,7 +1219,7 @@ __device__ __forceinline__ void static_feed(const StaticView &S, const int32_t *
 template <class L>
 __device__ __forceinline__ void dyn_feed(const DynSeq &D, const int32_t *tok, int64_t count,
                                          uint32_t vocab, int lane, DynCursor<L> &c,
-                                         uint32_t &fault, bool have_first = false,
+                                         uint32_t &fault, bool use_asm, bool have_first = false,
                                          uint32_t first = 0)
 {
     bool stop = false;
@@ -1221,7 +1232,9 @@ __device__ __forceinline__ void dyn_feed(const DynSeq &D, const int32_t *tok, in
         c.pf_ok = false;
         const uint32_t n_chunk = c.n;
         int fed = 0;
-        if constexpr (L::kSlots == 16) {
+        bool in_asm = false;
+        if constexpr (L::kSlots == 16) in_asm = use_asm;
+        if constexpr (L::kSlots == 16) if (in_asm) {
             // values the two waves of a workgroup hold jointly count as per-lane for
             // the compiler; the assembly wants them in scalar registers
             const uint32_t nbk = uni(D.n_buckets), m_u = uni((uint32_t)m), vocab_u = uni(vocab);
@@ -1230,12 +1243,6 @@ __device__ __forceinline__ void dyn_feed(const DynSeq &D, const int32_t *tok, in
             c.n = uni(c.n); c.n_states = uni(c.n_states); c.last = uni(c.last);
             c.n_trans = uni(c.n_trans); c.P = uni(c.P);
             const uint32_t lo = (uint32_t)(lane & 15) * 8u;
-            if (c.P == kNil && m > 0) {
-                // the sequence's very first token
-                const uint32_t t = lane_get(tv, 0);
-                if (t >= vocab) { stop = true; fault |= SAM_STATUS_TOKEN_BIT; }
-                else { dyn_expand<L>(D, t, kNil, lane, c, fault); fed = 1; }
-            }
             if (!stop && fed < m) {
                 uint32_t i = uni((uint32_t)fed), flt = 0;
                 uint32_t r0 = uni((c.RP.len & 0xFFFFu) | (c.RP.link << 16));
@@ -1256,7 +1263,8 @@ __device__ __forceinline__ void dyn_feed(const DynSeq &D, const int32_t *tok, in
                     if (!flt) fault |= SAM_STATUS_TOKEN_BIT;
                 }
             }
-        } else {
+        }
+        if (!in_asm) {
             for (; fed < m; fed++) {
                 const uint32_t t = lane_get(tv, fed);
                 if (t >= vocab) { stop = true; fault |= SAM_STATUS_TOKEN_BIT; break; }
@@ -1360,7 +1368,7 @@ __device__ __forceinline__ void emit_draft(const StaticView &S, const BatchView 
 // tokens[offsets[b] : offsets[b+1]) and nothing is written to the draft
 // outputs.  Otherwise: sequence b is fed the first counts[b] tokens of
 // tokens[b * max_accept ...], then source selection and draft gather.
-template <class L, bool kIngest>
+template <class L, bool kIngest, bool kAsm>
 __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B,
                                                         const int32_t *__restrict__ seq_map,
                                                         const int32_t *__restrict__ tokens,
@@ -1417,14 +1425,14 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
 
     if (wave == 0) {
         uint32_t s = lane_get(mv, 0), l = lane_get(mv, 1), e = lane_get(mv, 2);
-        if (B.has_static) static_feed(S, tok, count, vocab, lane, s, l, e, fault, !kIngest, first);
+        if (B.has_static) static_feed(S, tok, count, vocab, lane, s, l, e, fault, kAsm, !kIngest, first);
         if (lane == 0) { sh[0] = s; sh[1] = l; sh[2] = e; sh[6] = fault & SAM_STATUS_INTERNAL_BIT; }
     } else {
         const DynSeq D = dyn_region<L>(B, b);
         DynCursor<L> c;
         cursor_from_lanes<L>(mv, c);
         c.rec_bytes = (uint32_t)B.max_states * 16u;
-        dyn_feed<L>(D, tok, count, vocab, lane, c, fault, !kIngest, first);
+        dyn_feed<L>(D, tok, count, vocab, lane, c, fault, kAsm, !kIngest, first);
         if (c.n != n0) flush_last<L>(D, c, lane);
         if (lane == 0) {
             sh[3] = c.P == kNil ? 0u : c.RP.len;
@@ -1457,7 +1465,7 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
 // the longest row of another and nothing is launched in between.  Step s reads
 // accepted[s, b, :] and counts[s, b] and writes row (s, b) of the outputs.  The
 // cursors stay in registers from step to step.
-template <class L>
+template <class L, bool kAsm>
 __global__ __launch_bounds__(128) void sam_replay_kernel(StaticView S, BatchView B, int n_steps,
                                                           const int32_t *__restrict__ accepted,
                                                           const int32_t *__restrict__ counts,
@@ -1491,9 +1499,9 @@ __global__ __launch_bounds__(128) void sam_replay_kernel(StaticView S, BatchView
         count = (int64_t)uni((uint32_t)count);
         if ((int64_t)n_cur + count > (int64_t)B.max_seq_len) { fault |= SAM_STATUS_CAPACITY_BIT; count = 0; }
         if (wave == 0) {
-            if (B.has_static) static_feed(S, tok, count, vocab, lane, s, l, e, fault);
+            if (B.has_static) static_feed(S, tok, count, vocab, lane, s, l, e, fault, kAsm);
         } else {
-            dyn_feed<L>(D, tok, count, vocab, lane, c, fault);
+            dyn_feed<L>(D, tok, count, vocab, lane, c, fault, kAsm);
             if (lane == 0) {
                 sh[3] = c.P == kNil ? 0u : c.RP.len;
                 sh[4] = c.P == kNil ? 0u : c.RP.endpos;
@@ -1631,25 +1639,21 @@ hipError_t launch_feed(const StaticView &S, const BatchView &B, const int32_t *s
                        int32_t *draft_len, int32_t *source, hipStream_t stream)
 {
     const dim3 grid(n_seqs), block(128);
-    if (offsets) {
-        if (B.compact)
-            hipLaunchKernelGGL((sam_feed_kernel<CompactDyn, true>), grid, block, 0, stream, S, B,
-                               seq_map, tokens, offsets, counts, match_len, draft, draft_len,
-                               source);
-        else
-            hipLaunchKernelGGL((sam_feed_kernel<WideDyn, true>), grid, block, 0, stream, S, B,
-                               seq_map, tokens, offsets, counts, match_len, draft, draft_len,
-                               source);
-    } else {
-        if (B.compact)
-            hipLaunchKernelGGL((sam_feed_kernel<CompactDyn, false>), grid, block, 0, stream, S, B,
-                               seq_map, tokens, offsets, counts, match_len, draft, draft_len,
-                               source);
-        else
-            hipLaunchKernelGGL((sam_feed_kernel<WideDyn, false>), grid, block, 0, stream, S, B,
-                               seq_map, tokens, offsets, counts, match_len, draft, draft_len,
-                               source);
+#define SAM_LAUNCH_FEED(LAYOUT, INGEST, ASM)                                                   \
+    hipLaunchKernelGGL((sam_feed_kernel<LAYOUT, INGEST, ASM>), grid, block, 0, stream, S, B,   \
+                       seq_map, tokens, offsets, counts, match_len, draft, draft_len, source)
+    const int which = (B.compact ? 4 : 0) | (offsets ? 2 : 0) | ((B.no_asm || (S.n_buckets >> 32)) ? 0 : 1);
+    switch (which) {
+    case 7: SAM_LAUNCH_FEED(CompactDyn, true, true); break;
+    case 6: SAM_LAUNCH_FEED(CompactDyn, true, false); break;
+    case 5: SAM_LAUNCH_FEED(CompactDyn, false, true); break;
+    case 4: SAM_LAUNCH_FEED(CompactDyn, false, false); break;
+    case 3: SAM_LAUNCH_FEED(WideDyn, true, true); break;
+    case 2: SAM_LAUNCH_FEED(WideDyn, true, false); break;
+    case 1: SAM_LAUNCH_FEED(WideDyn, false, true); break;
+    default: SAM_LAUNCH_FEED(WideDyn, false, false); break;
     }
+#undef SAM_LAUNCH_FEED
     return hipGetLastError();
 }
 
@@ -1658,12 +1662,16 @@ hipError_t launch_replay(const StaticView &S, const BatchView &B, int n_steps,
                          int32_t *draft, int32_t *draft_len, int32_t *source, hipStream_t stream)
 {
     const dim3 grid(B.batch), block(128);
-    if (B.compact)
-        hipLaunchKernelGGL((sam_replay_kernel<CompactDyn>), grid, block, 0, stream, S, B, n_steps,
-                           accepted, counts, match_len, draft, draft_len, source);
-    else
-        hipLaunchKernelGGL((sam_replay_kernel<WideDyn>), grid, block, 0, stream, S, B, n_steps,
-                           accepted, counts, match_len, draft, draft_len, source);
+#define SAM_LAUNCH_REPLAY(LAYOUT, ASM)                                                         \
+    hipLaunchKernelGGL((sam_replay_kernel<LAYOUT, ASM>), grid, block, 0, stream, S, B, n_steps, \
+                       accepted, counts, match_len, draft, draft_len, source)
+    const bool cxx = B.no_asm || (S.n_buckets >> 32);
+    if (B.compact) {
+        if (cxx) SAM_LAUNCH_REPLAY(CompactDyn, false); else SAM_LAUNCH_REPLAY(CompactDyn, true);
+    } else {
+        if (cxx) SAM_LAUNCH_REPLAY(WideDyn, false); else SAM_LAUNCH_REPLAY(WideDyn, true);
+    }
+#undef SAM_LAUNCH_REPLAY
     return hipGetLastError();
 }
 

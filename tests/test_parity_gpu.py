@@ -118,6 +118,26 @@ def test_tight_slot_tables(seed, vocab, mode, T):
     assert_same(g, r)
 
 
+@pytest.mark.parametrize("mode", [4, 6])
+@pytest.mark.parametrize("seed,vocab", [(50, 2), (51, 5), (52, 300), (53, 32000)])
+def test_cxx_token_loops(seed, vocab, mode):
+    """The C++ form of Transfer and Expand (what runs for the wide layout, for a
+    sequence's first token and for corpora beyond 2^32 buckets) on the compact
+    layout, where the assembly form runs otherwise; also with tight slot tables."""
+    from paper_2411_10666_amd import binding as sam
+    B, T, A, L, steps = 10, 400, 7, 8, 60
+    _say("C++ token loops seed=%d vocab=%d mode=%d" % (seed, vocab, mode))
+    corpus, prompts, acc, counts = _random_case(seed, vocab, 3000, B, T, A, L, steps)
+    sam.sam_set_layout_override(mode)
+    try:
+        g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L)
+    finally:
+        sam.sam_set_layout_override(0)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r)
+
+
 def test_wide_layout_chosen_for_large_vocab():
     """A vocabulary above 2^17 does not fit the compact slot key."""
     vocab = 200_000
