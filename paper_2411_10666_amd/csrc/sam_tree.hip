@@ -8,11 +8,38 @@
 
 namespace sam {
 
+namespace {
+
+// Maximum of a value over the 64 lanes, the same in every lane.  Within a row of
+// 16 lanes by four data-parallel-primitive moves (a butterfly would need the LDS
+// crossbar, whose round trip is what a pop of the queue would then be spent on),
+// across the four rows through the scalar unit.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x)
+{
+    uint32_t y;
+    y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0xB1, 0xF, 0xF, false);   // lanes i ^ 1
+    x = x > y ? x : y;
+    y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x4E, 0xF, 0xF, false);   // lanes i ^ 2
+    x = x > y ? x : y;
+    y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x141, 0xF, 0xF, false);  // 7 - i in each half row
+    x = x > y ? x : y;
+    y = (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x140, 0xF, 0xF, false);  // 15 - i in each row
+    x = x > y ? x : y;
+    const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)x, 0);
+    const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
+    const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)x, 32);
+    const uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+    const uint32_t ab = a > b ? a : b, cd = c > d ? c : d;
+    return ab > cd ? ab : cd;
+}
+
+}  // namespace
+
 // Tree draft by best-first expansion over the top-k successors (Algorithm 4),
 // one wavefront per sequence.  The priority queue lives in LDS as an append-only
 // array; an entry's key packs (probability bits, ~push index), so the maximum
 // key is the largest probability and, among equals, the entry pushed first.  A
-// pop is a strided scan plus a wave reduction; the k children of the popped
+// pop is a strided scan plus two 32-bit wave reductions; the k children of the popped
 // state are fetched by k lanes in one request and appended in table order.
 // Probabilities are float products rounded once per edge.
 __global__ __launch_bounds__(64) void sam_tree_kernel(StaticView S, BatchView B, int max_size,
@@ -46,10 +73,11 @@ __global__ __launch_bounds__(64) void sam_tree_kernel(StaticView S, BatchView B,
                 const unsigned long long key = qkey[i];
                 best = key > best ? key : best;
             }
-            for (int off = 32; off > 0; off >>= 1) {
-                const unsigned long long o = __shfl_xor(best, off);
-                best = o > best ? o : best;
-            }
+            // the largest 64-bit key: the largest upper half, then the largest lower
+            // half among the lanes that hold that upper half
+            const uint32_t hi = wave_max_u32((uint32_t)(best >> 32));
+            const uint32_t lo = wave_max_u32((uint32_t)(best >> 32) == hi ? (uint32_t)best : 0u);
+            best = ((unsigned long long)hi << 32) | lo;
             if (best == 0) break;                       // queue empty
             const uint32_t idx = 0xFFFFFFFFu - (uint32_t)best;
             const float p = __uint_as_float((uint32_t)(best >> 32));
