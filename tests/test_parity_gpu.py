@@ -602,3 +602,51 @@ def test_membench_gives_plausible_figures():
         with pytest.raises(sam.SamError) as e:
             sam.sam_membench(*args)
         assert e.value.code == sam.SAM_EINVAL
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_random_cases_in_every_mode(block):
+    """50 small random cases per block: vocabulary, batch, lengths, row and draft sizes
+    drawn at random, tokens that repeat themselves, copy the corpus or copy the prompt,
+    and the library mode (assembly or C++ token loops, compact or wide tables, normal
+    or tight slot tables) drawn at random too."""
+    from paper_2411_10666_amd import binding as sam
+    for seed in range(7000 + 50 * block, 7050 + 50 * block):
+        rng = np.random.default_rng(seed)
+        vocab = int(rng.choice([2, 3, 4, 6, 20, 200, 5000, 32000, 100000]))
+        B, T = int(rng.integers(1, 40)), int(rng.integers(20, 1200))
+        A, L = int(rng.integers(1, 20)), int(rng.integers(1, 40))
+        ncorp = int(rng.integers(0, 4000))
+        mode = int(rng.choice([0, 0, 1, 2, 3, 4, 6]))
+        corpus = rng.integers(0, vocab, size=ncorp).astype(np.int32) if ncorp > 10 else None
+        prompts = [rng.integers(0, vocab, size=int(rng.integers(0, T // 2 + 1))).astype(np.int32)
+                   for _ in range(B)]
+        used = np.array([len(p) for p in prompts])
+        rows_c, rows_a = [], []
+        for _ in range(int(rng.integers(5, 80))):
+            c = np.minimum(rng.integers(0, A + 1, size=B), T - used)
+            a = rng.integers(0, vocab, size=(B, A)).astype(np.int32)
+            for b in range(B):
+                r = rng.random()
+                if c[b] >= 2 and r < 0.25:
+                    a[b, 1:] = a[b, 0]
+                elif corpus is not None and 2 <= c[b] < len(corpus) and r < 0.6:
+                    j = int(rng.integers(0, len(corpus) - c[b]))
+                    a[b, :c[b]] = corpus[j:j + c[b]]
+                elif 2 <= c[b] <= len(prompts[b]) and r < 0.8:
+                    j = int(rng.integers(0, len(prompts[b]) - c[b] + 1))
+                    a[b, :c[b]] = prompts[b][j:j + c[b]]
+            rows_c.append(c)
+            rows_a.append(a)
+            used += c
+        counts = np.array(rows_c, dtype=np.int32)
+        acc = np.array(rows_a, dtype=np.int32)
+        _say("random case seed=%d vocab=%d B=%d T=%d A=%d L=%d mode=%d" % (seed, vocab, B, T, A, L, mode))
+        sam.sam_set_layout_override(mode)
+        try:
+            g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L)
+        finally:
+            sam.sam_set_layout_override(0)
+        r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+        assert status == 0, seed
+        assert_same(g, r)
