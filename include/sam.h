@@ -295,8 +295,11 @@ int sam_batch_status(const sam_batch *batch, uint32_t *status, void *hip_stream)
  * slot tables as tightly as correctness allows (max_seq_len + 16 slots instead
  * of twice that), so that nearly full buckets and sweeps into the next bucket,
  * rare otherwise, happen all the time; bit 2 makes its kernels run the C++ form
- * of the two token loops instead of the assembly one.  mode 0 restores the
- * defaults.  Results are identical in every mode.
+ * of the two token loops instead of the assembly one; bit 3 makes every later
+ * sam_build size the corpus automaton's transition table at 4.5 GiB whatever the
+ * corpus (about that much host and device memory), so that table offsets beyond
+ * 32 bits are reached with a corpus that builds in a moment.  mode 0 restores
+ * the defaults.  Results are identical in every mode.
  */
 int sam_set_layout_override(int mode);
 

@@ -21,7 +21,9 @@ namespace {
 
 thread_local std::string g_err;
 int g_layout_override = 0;   // bit 0: always the wide layout, bit 1: tight slot tables,
-                             // bit 2: C++ token loops
+                             // bit 2: C++ token loops, bit 3: corpus table beyond 4 GiB
+// buckets of 128 bytes that make a transition table of 4.5 GiB
+constexpr uint64_t kHugeTableBuckets = (1ull << 25) + (1ull << 22);
 HostSam::ProgressFn g_progress = nullptr;
 void *g_progress_user = nullptr;
 
@@ -132,7 +134,8 @@ static int build_common(const int32_t *tokens, int64_t n, int32_t vocab, bool up
     std::string err;
     int rc;
     try {
-        rc = c->host.build(tokens, n, vocab, err, g_progress, g_progress_user);
+        rc = c->host.build(tokens, n, vocab, err, g_progress, g_progress_user,
+                           (g_layout_override & 8) ? kHugeTableBuckets : 0);
     } catch (const std::bad_alloc &) {
         rc = SAM_ENOMEM;
         err = "sam_build: out of host memory";
@@ -572,7 +575,7 @@ int sam_set_progress_callback(sam_progress_fn fn, void *user)
 
 int sam_set_layout_override(int mode)
 {
-    if (mode < 0 || mode > 7) return fail(SAM_EINVAL, "sam_set_layout_override: mode is 0 .. 7");
+    if (mode < 0 || mode > 15) return fail(SAM_EINVAL, "sam_set_layout_override: mode is 0 .. 15");
     g_layout_override = mode;
     return SAM_OK;
 }

@@ -74,7 +74,7 @@ inline uint64_t probe(const Slot *slots, uint64_t n_buckets, uint32_t state, uin
 }  // namespace
 
 int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string &err,
-                   ProgressFn progress, void *user)
+                   ProgressFn progress, void *user, uint64_t min_buckets)
 {
     if (!tokens || n < 1 || n > 0x7FFFFFFELL || vocab_ < 1) {
         err = "sam_build: need tokens != NULL, 1 <= n_tokens <= 2^31-2, vocab >= 1";
@@ -89,6 +89,7 @@ int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string
     n_tokens = n;
     vocab = vocab_;
     n_buckets = static_buckets_for(n);
+    if (n_buckets < min_buckets) n_buckets = min_buckets;
     const uint64_t n_slots = n_buckets * kBucketSlots;
     if (n_slots >= 0xFFFFFFFFull) {
         err = "sam_build: corpus too large for 32-bit slot indices";
@@ -345,7 +346,8 @@ int HostSam::load(const char *path, std::string &err)
         rc = SAM_EINVAL;
     } else if (h.n_tokens < 1 || h.n_tokens > 0x7FFFFFFELL || h.vocab < 1 || h.vocab > 0x7FFFFFFFLL ||
                h.n_states < 2 || h.n_states > 2 * (uint64_t)h.n_tokens + 1 ||
-               h.n_buckets != static_buckets_for(h.n_tokens)) {
+               h.n_buckets < static_buckets_for(h.n_tokens) ||
+               h.n_buckets * kBucketSlots >= 0xFFFFFFFFull) {
         err = std::string("sam_corpus_load: inconsistent header in ") + path;
         rc = SAM_EINVAL;
     }

@@ -53,8 +53,9 @@ struct HostSam {
     // returns SAM_OK or an error code; message in err.  `progress` (may be
     // null) is called now and then with a phase name and done/total counts.
     typedef void (*ProgressFn)(const char *phase, int64_t done, int64_t total, void *user);
+    // min_buckets (testing): a transition table of at least that many buckets.
     int build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string &err,
-              ProgressFn progress = nullptr, void *user = nullptr);
+              ProgressFn progress = nullptr, void *user = nullptr, uint64_t min_buckets = 0);
 
     // Write the built automaton to a file / read it back (same machine byte
     // order, same library layout version).  The top-k table is not stored.

@@ -107,7 +107,7 @@ struct SeqMeta {
 };
 
 // (state, token) -> 32-bit hash; the same function on host and device
-#if defined(__HIPCC__) || defined(__CUDACC__)
+#if defined(__HIPCC__)
 __host__ __device__
 #endif
 inline uint32_t hash_key(uint32_t state, uint32_t token)
@@ -122,7 +122,7 @@ inline uint32_t hash_key(uint32_t state, uint32_t token)
 }
 
 // map a 32-bit hash onto [0, n_buckets) without a modulo
-#if defined(__HIPCC__) || defined(__CUDACC__)
+#if defined(__HIPCC__)
 __host__ __device__
 #endif
 inline uint64_t bucket_of(uint32_t h, uint64_t n_buckets)

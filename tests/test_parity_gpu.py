@@ -118,6 +118,37 @@ def test_tight_slot_tables(seed, vocab, mode, T):
     assert_same(g, r)
 
 
+def test_static_table_beyond_4_gib():
+    """A corpus automaton whose transition table is 4.5 GiB (testing mode, bit 3): a
+    ninth of the lookups land in buckets whose byte offset does not fit 32 bits, so the
+    64-bit address arithmetic of Transfer runs with a corpus that builds in a moment.
+    Run with the assembly token loops and with the C++ ones on the same automaton."""
+    import torch
+    from paper_2411_10666_amd import binding as sam
+    spec = CONFIGS["cfg1"].scaled(corpus_tokens=40_000, batch=24, prompt_len=300, gen_len=500)
+    w = make_workload(spec)
+    prompts = [w.prompts[b] for b in range(spec.batch)]
+    r, _ = run_oracle(w.corpus, prompts, w.accepted, w.counts, spec.max_accept, spec.draft_len)
+    assert sum(int((x["source"] == 2).sum()) for x in r) > 200
+    _say("static table beyond 4 GiB: build")
+    sam.sam_set_layout_override(8)
+    try:
+        corpus = sam.sam_build(w.corpus, spec.vocab)
+        assert sam.sam_corpus_info(corpus)[2] > (1 << 32) + (1 << 28)
+        for mode in (8, 12):
+            _say("static table beyond 4 GiB: steps, mode=%d" % mode)
+            sam.sam_set_layout_override(mode)
+            g, status, _ = run_gpu(w.corpus, spec.vocab, prompts, w.accepted, w.counts,
+                                   spec.max_seq_len, spec.max_accept, spec.draft_len,
+                                   gpu_corpus=corpus)
+            assert status == 0
+            assert_same(g, r)
+    finally:
+        sam.sam_set_layout_override(0)
+    del corpus
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("mode", [4, 6])
 @pytest.mark.parametrize("seed,vocab", [(50, 2), (51, 5), (52, 300), (53, 32000)])
 def test_cxx_token_loops(seed, vocab, mode):
