@@ -184,6 +184,37 @@ int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
                    int32_t l_bias, void *hip_stream, sam_batch **out);
 
 /*
+ * sam_batch_init for callers that cannot allocate device memory: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * The batch's tables (per-sequence text, state records, transition slots,
+ * cursors, status word), which sam_batch_init allocates, live instead in a fixed
+ * buffer of SAM_NOALLOC_MAX_BYTES that is part of the library's device code, one
+ * copy per GPU, held until the process ends.  The call and every later call on
+ * the returned batch (sam_batch_step, _replay, _debug, _sizes, _tree_draft, _free)
+ * allocate and free no device memory.
+ *   prompt_offsets_host : host, int64 [batch+1]; the same values as the device
+ *                    array.  They are validated from this copy, so the call does
+ *                    not read anything back and does not synchronise.
+ *   all other arguments as for sam_batch_init.
+ * Differences from sam_batch_init: asynchronous; a prompt token outside the
+ * vocabulary is reported by sam_batch_status (SAM_STATUS_TOKEN), not by the
+ * return code.  Sizes whose tables do not fit the buffer are refused with
+ * SAM_EINVAL (the message names both sizes).  One such batch per GPU at a time:
+ * a second call before sam_batch_free of the first returns SAM_EINVAL.  The
+ * buffer keeps the previous batch's contents and is cleared by the call, on the
+ * given stream, with kernels (no memset nodes); work of the previous batch that
+ * is still running on another stream would race with it.
+ * The handle is owned by the library; release it with sam_batch_free.
+ * Errors: SAM_EINVAL, SAM_ECAPACITY (a prompt longer than max_seq_len),
+ * SAM_EDEVICE.
+ */
+#define SAM_NOALLOC_MAX_BYTES (32 * 1024 * 1024)
+int sam_batch_init_noalloc(const sam_corpus *corpus, const int32_t *prompt_tokens,
+                           const int64_t *prompt_offsets, const int64_t *prompt_offsets_host,
+                           int32_t batch, int32_t vocab, int32_t max_seq_len, int32_t max_accept,
+                           int32_t draft_len, int32_t l_bias, void *hip_stream, sam_batch **out);
+
+/*
  * One generation round for the whole batch, one kernel launch.  For sequence b
  * the first counts[b] tokens of row b of `accepted` are fed in order: static
  * Transfer per token (Algorithm 1), dynamic match on the automaton as it stands

@@ -27,7 +27,7 @@ EXPORTS = [
     "sam_batch_reset", "sam_set_progress_callback",
     "sam_batch_set_threshold", "sam_corpus_build_topk", "sam_corpus_export_topk",
     "sam_batch_tree_draft", "sam_corpus_save", "sam_corpus_load", "sam_corpus_load_host_only",
-    "sam_batch_replay", "sam_membench",
+    "sam_batch_replay", "sam_membench", "sam_batch_init_noalloc",
 ]
 
 
@@ -60,6 +60,8 @@ def _load():
     L.sam_corpus_free.argtypes = [vp]
     L.sam_corpus_free.restype = None
     L.sam_batch_init.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, C.POINTER(vp)]
+    L.sam_batch_init_noalloc.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp,
+                                         C.POINTER(vp)]
     L.sam_batch_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
     L.sam_set_progress_callback.argtypes = [PROGRESS_FN, vp]
     L.sam_batch_set_threshold.argtypes = [vp, i32]
@@ -238,6 +240,27 @@ def sam_batch_init(corpus, prompt_tokens, prompt_offsets, batch: int, vocab: int
                                _dev_ptr(prompt_offsets, torch.int64, "prompt_offsets"),
                                batch, vocab, max_seq_len, max_accept, draft_len, l_bias,
                                _stream_ptr(stream), C.byref(h)))
+    return Batch(h, corpus, batch, max_accept, draft_len)
+
+
+NOALLOC_MAX_BYTES = 32 * 1024 * 1024
+
+
+def sam_batch_init_noalloc(corpus, prompt_tokens, prompt_offsets, prompt_offsets_host, batch: int,
+                           vocab: int, max_seq_len: int, max_accept: int, draft_len: int,
+                           l_bias: int = 0, stream=None) -> Batch:
+    """prompt_offsets_host: int64 numpy array, the host copy of prompt_offsets."""
+    import torch
+    ho = np.ascontiguousarray(prompt_offsets_host, dtype=np.int64)
+    if ho.size != batch + 1:
+        raise ValueError("prompt_offsets_host must hold batch + 1 values")
+    h = C.c_void_p()
+    _check(_lib.sam_batch_init_noalloc(corpus._h if corpus is not None else None,
+                                       _dev_ptr(prompt_tokens, torch.int32, "prompt_tokens"),
+                                       _dev_ptr(prompt_offsets, torch.int64, "prompt_offsets"),
+                                       ho.ctypes.data_as(C.c_void_p), batch, vocab, max_seq_len,
+                                       max_accept, draft_len, l_bias, _stream_ptr(stream),
+                                       C.byref(h)))
     return Batch(h, corpus, batch, max_accept, draft_len)
 
 

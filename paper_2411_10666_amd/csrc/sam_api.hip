@@ -6,6 +6,7 @@
 #include <stdint.h>
 #include <stdio.h>
 
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -47,6 +48,14 @@ int fail_hip(const char *what, hipError_t e)
 
 }  // namespace
 
+// Table space of the batch made by sam_batch_init_noalloc: device memory that is
+// part of the loaded code object, so no call ever has to allocate it.  Every GPU
+// the library runs on holds its own copy at its own address for the life of the
+// process.  In host code the name below is only a handle for hipGetSymbolAddress;
+// the address kernels and fills receive is the one that call returns.
+constexpr size_t kNoAllocBytes = (size_t)SAM_NOALLOC_MAX_BYTES;
+static __device__ __align__(256) unsigned char g_noalloc_scratch[kNoAllocBytes];
+
 struct sam_corpus {
     HostSam    host;
     bool       on_device = false;
@@ -61,7 +70,41 @@ struct sam_batch {
     const sam_corpus *corpus = nullptr;
     BatchView         view = {};
     int64_t           device_bytes = 0;
+    int               noalloc_device = -1;   // >= 0: lives in that device's fixed buffer
 };
+
+namespace {
+
+// one fixed-buffer batch per device: its handle, the buffer's device address
+// (looked up once per device) and whether the handle is handed out
+constexpr int kMaxDevices = 64;
+struct NoAllocSlot {
+    sam_batch      handle;
+    unsigned char *base = nullptr;
+    bool           busy = false;
+};
+NoAllocSlot g_noalloc[kMaxDevices];
+std::mutex  g_noalloc_mu;
+
+}  // namespace
+
+// Address of the current device's copy of the fixed buffer, looked up once per
+// device with that device current (the first lookup makes the runtime load this
+// file's device code on that GPU, which is when the buffer comes to exist there).
+// Call with g_noalloc_mu held.
+static hipError_t noalloc_base_locked(int dev, unsigned char **base)
+{
+    NoAllocSlot &slot = g_noalloc[dev];
+    if (!slot.base) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_noalloc_scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        slot.base = (unsigned char *)p;
+    }
+    *base = slot.base;
+    return hipSuccess;
+}
 
 extern "C" {
 
@@ -121,6 +164,13 @@ static int corpus_upload(sam_corpus *c)
     c->view.n_states = h.n_states;
     c->device_bytes = (int64_t)(b_text + b_lr + b_root + b_slots);
     c->on_device = true;
+    if (c->device >= 0 && c->device < kMaxDevices) {
+        // a set-up call: do the one-time lookup of the fixed buffer here, so that a later
+        // sam_batch_init_noalloc on this device has nothing left to load
+        std::lock_guard<std::mutex> lock(g_noalloc_mu);
+        unsigned char *unused = nullptr;
+        (void)noalloc_base_locked(c->device, &unused);
+    }
     return SAM_OK;
 }
 
@@ -307,6 +357,12 @@ void sam_corpus_free(sam_corpus *c)
 
 static void batch_release(sam_batch *b)
 {
+    if (b->noalloc_device >= 0) {
+        // nothing to free: the tables are the device's fixed buffer
+        std::lock_guard<std::mutex> lock(g_noalloc_mu);
+        g_noalloc[b->noalloc_device].busy = false;
+        return;
+    }
     if (b->view.dyn_text) (void)hipFree(b->view.dyn_text);
     if (b->view.dyn_rec) (void)hipFree(b->view.dyn_rec);
     if (b->view.dyn_slots) (void)hipFree(b->view.dyn_slots);
@@ -315,60 +371,59 @@ static void batch_release(sam_batch *b)
     delete b;
 }
 
-int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
-                   const int64_t *prompt_offsets, int32_t batch, int32_t vocab,
-                   int32_t max_seq_len, int32_t max_accept, int32_t draft_len, int32_t l_bias,
-                   void *hip_stream, sam_batch **out)
+// Argument checks shared by the two init calls; resolves the vocabulary.
+static int batch_check_args(const char *fn, const sam_corpus *corpus, const int32_t *prompt_tokens,
+                            const int64_t *prompt_offsets, int32_t batch, int32_t &vocab,
+                            int32_t max_seq_len, int32_t max_accept, int32_t draft_len)
 {
-    if (!out) return fail(SAM_EINVAL, "sam_batch_init: out is NULL");
-    *out = nullptr;
+    const std::string f(fn);
     if (!prompt_tokens || !prompt_offsets)
-        return fail(SAM_EINVAL, "sam_batch_init: prompt_tokens / prompt_offsets is NULL");
-    if (batch < 1) return fail(SAM_EINVAL, "sam_batch_init: batch must be >= 1");
+        return fail(SAM_EINVAL, f + ": prompt_tokens / prompt_offsets is NULL");
+    if (batch < 1) return fail(SAM_EINVAL, f + ": batch must be >= 1");
     if (max_seq_len < 1 || max_seq_len > (1 << 28))
-        return fail(SAM_EINVAL, "sam_batch_init: max_seq_len must be in 1 .. 2^28");
+        return fail(SAM_EINVAL, f + ": max_seq_len must be in 1 .. 2^28");
     if (max_accept < 1 || max_accept > 4096)
-        return fail(SAM_EINVAL, "sam_batch_init: max_accept must be in 1 .. 4096");
+        return fail(SAM_EINVAL, f + ": max_accept must be in 1 .. 4096");
     if (draft_len < 1 || draft_len > 1024)
-        return fail(SAM_EINVAL, "sam_batch_init: draft_len must be in 1 .. 1024");
+        return fail(SAM_EINVAL, f + ": draft_len must be in 1 .. 1024");
     if (corpus && !corpus->on_device)
-        return fail(SAM_EINVAL, "sam_batch_init: corpus was built host-only");
+        return fail(SAM_EINVAL, f + ": corpus was built host-only");
     if (corpus) {
         int dev = -1;
         HIP_TRY(hipGetDevice(&dev));
         if (dev != corpus->device)
-            return fail(SAM_EINVAL, "sam_batch_init: the corpus lives on device " +
+            return fail(SAM_EINVAL, f + ": the corpus lives on device " +
                                         std::to_string(corpus->device) + ", the current device is " +
                                         std::to_string(dev));
         vocab = corpus->host.vocab;
     }
-    if (vocab < 1) return fail(SAM_EINVAL, "sam_batch_init: vocab must be >= 1");
-    hipStream_t stream = (hipStream_t)hip_stream;
+    if (vocab < 1) return fail(SAM_EINVAL, f + ": vocab must be >= 1");
+    return SAM_OK;
+}
 
-    // the offsets decide how far each wave reads: check them before any launch
-    std::vector<int64_t> offs;
-    try {
-        offs.resize((size_t)batch + 1);
-    } catch (const std::bad_alloc &) {
-        return fail(SAM_ENOMEM, "sam_batch_init: out of host memory");
-    }
-    HIP_TRY(hipMemcpyAsync(offs.data(), prompt_offsets, offs.size() * sizeof(int64_t),
-                           hipMemcpyDeviceToHost, stream));
-    HIP_TRY(hipStreamSynchronize(stream));
-    if (offs[0] < 0) return fail(SAM_EINVAL, "sam_batch_init: prompt_offsets[0] < 0");
+static int batch_check_offsets(const char *fn, const int64_t *offs, int32_t batch,
+                               int32_t max_seq_len)
+{
+    const std::string f(fn);
+    if (offs[0] < 0) return fail(SAM_EINVAL, f + ": prompt_offsets[0] < 0");
     for (int32_t b = 0; b < batch; b++) {
         const int64_t len = offs[b + 1] - offs[b];
-        if (len < 0) return fail(SAM_EINVAL, "sam_batch_init: prompt_offsets must not decrease");
+        if (len < 0) return fail(SAM_EINVAL, f + ": prompt_offsets must not decrease");
         if (len > max_seq_len)
-            return fail(SAM_ECAPACITY, "sam_batch_init: prompt " + std::to_string(b) + " has " +
+            return fail(SAM_ECAPACITY, f + ": prompt " + std::to_string(b) + " has " +
                                            std::to_string(len) + " tokens, max_seq_len is " +
                                            std::to_string(max_seq_len));
     }
+    return SAM_OK;
+}
 
-    sam_batch *bt = new (std::nothrow) sam_batch;
-    if (!bt) return fail(SAM_ENOMEM, "sam_batch_init: out of host memory");
-    bt->corpus = corpus;
-    BatchView &v = bt->view;
+// Sizes of the per-sequence tables for these parameters.
+struct BatchBytes { size_t text, rec, slots, meta; };
+
+static BatchBytes batch_configure(BatchView &v, bool has_static, int32_t batch, int32_t vocab,
+                                  int32_t max_seq_len, int32_t max_accept, int32_t draft_len,
+                                  int32_t l_bias)
+{
     v.batch = batch;
     v.vocab = vocab;
     v.max_seq_len = (uint32_t)max_seq_len;
@@ -387,23 +442,58 @@ int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
     v.l_bias = l_bias;
     v.l_threshold = -1;
     v.no_asm = (g_layout_override & 4) ? 1 : 0;
-    v.has_static = corpus ? 1 : 0;
-    const size_t b_text = (size_t)batch * max_seq_len * sizeof(int32_t);
-    const size_t b_rec = (size_t)batch * v.max_states * rec_bytes;
-    const size_t b_slots = (size_t)batch * v.dyn_buckets * 128;
-    const size_t b_meta = (size_t)batch * sizeof(SeqMeta);
+    v.has_static = has_static ? 1 : 0;
+    BatchBytes b;
+    b.text = (size_t)batch * max_seq_len * sizeof(int32_t);
+    b.rec = (size_t)batch * v.max_states * rec_bytes;
+    b.slots = (size_t)batch * v.dyn_buckets * 128;
+    b.meta = (size_t)batch * sizeof(SeqMeta);
+    return b;
+}
+
+int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
+                   const int64_t *prompt_offsets, int32_t batch, int32_t vocab,
+                   int32_t max_seq_len, int32_t max_accept, int32_t draft_len, int32_t l_bias,
+                   void *hip_stream, sam_batch **out)
+{
+    if (!out) return fail(SAM_EINVAL, "sam_batch_init: out is NULL");
+    *out = nullptr;
+    int rc = batch_check_args("sam_batch_init", corpus, prompt_tokens, prompt_offsets, batch,
+                              vocab, max_seq_len, max_accept, draft_len);
+    if (rc != SAM_OK) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    // the offsets decide how far each wave reads: check them before any launch
+    std::vector<int64_t> offs;
+    try {
+        offs.resize((size_t)batch + 1);
+    } catch (const std::bad_alloc &) {
+        return fail(SAM_ENOMEM, "sam_batch_init: out of host memory");
+    }
+    HIP_TRY(hipMemcpyAsync(offs.data(), prompt_offsets, offs.size() * sizeof(int64_t),
+                           hipMemcpyDeviceToHost, stream));
+    HIP_TRY(hipStreamSynchronize(stream));
+    rc = batch_check_offsets("sam_batch_init", offs.data(), batch, max_seq_len);
+    if (rc != SAM_OK) return rc;
+
+    sam_batch *bt = new (std::nothrow) sam_batch;
+    if (!bt) return fail(SAM_ENOMEM, "sam_batch_init: out of host memory");
+    bt->corpus = corpus;
+    BatchView &v = bt->view;
+    const BatchBytes bb = batch_configure(v, corpus != nullptr, batch, vocab, max_seq_len,
+                                          max_accept, draft_len, l_bias);
     hipError_t e;
-    if ((e = hipMalloc((void **)&v.dyn_text, b_text)) != hipSuccess ||
-        (e = hipMalloc((void **)&v.dyn_rec, b_rec)) != hipSuccess ||
-        (e = hipMalloc((void **)&v.dyn_slots, b_slots)) != hipSuccess ||
-        (e = hipMalloc((void **)&v.meta, b_meta)) != hipSuccess ||
+    if ((e = hipMalloc((void **)&v.dyn_text, bb.text)) != hipSuccess ||
+        (e = hipMalloc((void **)&v.dyn_rec, bb.rec)) != hipSuccess ||
+        (e = hipMalloc((void **)&v.dyn_slots, bb.slots)) != hipSuccess ||
+        (e = hipMalloc((void **)&v.meta, bb.meta)) != hipSuccess ||
         (e = hipMalloc((void **)&v.status, 256)) != hipSuccess) {
         batch_release(bt);
         return fail_hip("sam_batch_init: hipMalloc", e);
     }
-    bt->device_bytes = (int64_t)(b_text + b_rec + b_slots + b_meta + 256);
+    bt->device_bytes = (int64_t)(bb.text + bb.rec + bb.slots + bb.meta + 256);
     StaticView S = corpus ? corpus->view : StaticView{};
-    if ((e = hipMemsetAsync(v.dyn_slots, 0xFF, b_slots, stream)) != hipSuccess ||
+    if ((e = hipMemsetAsync(v.dyn_slots, 0xFF, bb.slots, stream)) != hipSuccess ||
         (e = launch_reset(v, nullptr, batch, stream)) != hipSuccess ||
         (e = launch_feed(S, v, nullptr, batch, prompt_tokens, prompt_offsets, nullptr, nullptr,
                          nullptr, nullptr, nullptr, stream)) != hipSuccess ||
@@ -419,6 +509,77 @@ int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
     if (st & SAM_STATUS_TOKEN) {
         batch_release(bt);
         return fail(SAM_ETOKEN, "sam_batch_init: a prompt token is outside [0, vocab)");
+    }
+    *out = bt;
+    return SAM_OK;
+}
+
+int sam_batch_init_noalloc(const sam_corpus *corpus, const int32_t *prompt_tokens,
+                           const int64_t *prompt_offsets, const int64_t *prompt_offsets_host,
+                           int32_t batch, int32_t vocab, int32_t max_seq_len, int32_t max_accept,
+                           int32_t draft_len, int32_t l_bias, void *hip_stream, sam_batch **out)
+{
+    static const char *fn = "sam_batch_init_noalloc";
+    if (!out) return fail(SAM_EINVAL, "sam_batch_init_noalloc: out is NULL");
+    *out = nullptr;
+    if (!prompt_offsets_host)
+        return fail(SAM_EINVAL, "sam_batch_init_noalloc: prompt_offsets_host is NULL");
+    int rc = batch_check_args(fn, corpus, prompt_tokens, prompt_offsets, batch, vocab, max_seq_len,
+                              max_accept, draft_len);
+    if (rc != SAM_OK) return rc;
+    rc = batch_check_offsets(fn, prompt_offsets_host, batch, max_seq_len);
+    if (rc != SAM_OK) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(SAM_EINVAL, "sam_batch_init_noalloc: device index beyond " +
+                                    std::to_string(kMaxDevices - 1));
+
+    BatchView v = {};
+    const BatchBytes bb = batch_configure(v, corpus != nullptr, batch, vocab, max_seq_len,
+                                          max_accept, draft_len, l_bias);
+    auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+    const size_t o_text = 0, o_rec = o_text + up(bb.text), o_slots = o_rec + up(bb.rec),
+                 o_meta = o_slots + up(bb.slots), o_status = o_meta + up(bb.meta),
+                 need = o_status + 256;
+    if (need > kNoAllocBytes)
+        return fail(SAM_EINVAL, "sam_batch_init_noalloc: these sizes need " + std::to_string(need) +
+                                    " bytes of table space, the fixed buffer holds " +
+                                    std::to_string(kNoAllocBytes) +
+                                    " (use sam_batch_init for larger batches)");
+
+    NoAllocSlot &slot = g_noalloc[dev];
+    unsigned char *base = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_noalloc_mu);
+        if (slot.busy)
+            return fail(SAM_EINVAL, "sam_batch_init_noalloc: the fixed buffer of this device is in "
+                                    "use by a batch that has not been freed");
+        hipError_t e = noalloc_base_locked(dev, &base);
+        if (e != hipSuccess) return fail_hip("sam_batch_init_noalloc: address of the fixed buffer", e);
+        slot.busy = true;
+    }
+    v.dyn_text = (int32_t *)(base + o_text);
+    v.dyn_rec = base + o_rec;
+    v.dyn_slots = base + o_slots;
+    v.meta = (SeqMeta *)(base + o_meta);
+    v.status = (uint32_t *)(base + o_status);
+    sam_batch *bt = &slot.handle;
+    bt->corpus = corpus;
+    bt->view = v;
+    bt->device_bytes = (int64_t)need;
+    bt->noalloc_device = dev;
+    // the buffer keeps what the last batch left: empty the slot tables, then fresh
+    // records, cursors and status word (the reset kernel), then the prompts
+    StaticView S = corpus ? corpus->view : StaticView{};
+    hipError_t e;
+    if ((e = launch_fill_empty(v.dyn_slots, bb.slots, stream)) != hipSuccess ||
+        (e = launch_reset(v, nullptr, batch, stream)) != hipSuccess ||
+        (e = launch_feed(S, v, nullptr, batch, prompt_tokens, prompt_offsets, nullptr, nullptr,
+                         nullptr, nullptr, nullptr, stream)) != hipSuccess) {
+        batch_release(bt);
+        return fail_hip("sam_batch_init_noalloc: launch", e);
     }
     *out = bt;
     return SAM_OK;

@@ -63,6 +63,9 @@ hipError_t launch_replay(const StaticView &S, const BatchView &B, int n_steps,
 // are cleared by the caller).  Otherwise: the listed sequences, slot tables included.
 hipError_t launch_reset(const BatchView &B, const int32_t *seq_map, int n_seqs,
                         hipStream_t stream);
+// Every byte of [base, base + bytes) becomes 0xFF (the empty slot key); bytes is a
+// multiple of 16.  A kernel, not a memset node, so that it may be captured in a graph.
+hipError_t launch_fill_empty(void *base, size_t bytes, hipStream_t stream);
 // Best-first tree drafts from the static cursor of every sequence (Algorithm 4).
 hipError_t launch_tree(const StaticView &S, const BatchView &B, int max_size, int32_t *tokens,
                        int32_t *parents, float *probs, int32_t *sizes, hipStream_t stream);

@@ -1573,6 +1573,14 @@ __global__ void sam_clear_slots_kernel(BatchView B, const int32_t *seq_map)
         base[i] = make_uint4(kNil, kNil, kNil, kNil);
 }
 
+// Fill a 16-byte aligned region with the empty key (every byte 0xFF).
+__global__ void sam_fill_empty_kernel(uint4 *base, size_t n16)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16;
+         i += (size_t)gridDim.x * blockDim.x)
+        base[i] = make_uint4(kNil, kNil, kNil, kNil);
+}
+
 __global__ void sam_debug_kernel(BatchView B, int32_t *s1, int32_t *l1, int32_t *s2, int32_t *l2,
                                  int32_t *text_len, int32_t *n_states, int32_t *n_trans)
 {
@@ -1686,6 +1694,16 @@ hipError_t launch_reset(const BatchView &B, const int32_t *seq_map, int n_seqs,
     }
     hipLaunchKernelGGL(sam_reset_kernel, dim3((n_seqs + 127) / 128), dim3(128), 0, stream, B,
                        seq_map, n_seqs);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_empty(void *base, size_t bytes, hipStream_t stream)
+{
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    const size_t want = (n16 + 255) / 256;
+    hipLaunchKernelGGL(sam_fill_empty_kernel, dim3((unsigned)(want < 4096 ? want : 4096)), dim3(256),
+                       0, stream, reinterpret_cast<uint4 *>(base), n16);
     return hipGetLastError();
 }
 
