@@ -380,6 +380,29 @@ def test_freq_worked_example_abcbc():
     assert pr[0] == np.float32(1.0) and pr[1] == np.float32(5 / 9)
 
 
+def test_prim_tie_goes_to_the_entry_pushed_first():
+    """Hand-worked "AAAB" (tests/golden/aaab_prim.txt): two queue entries with the
+    probability 1/4, exact in float, pushed at different pops; the one pushed first is
+    expanded first.  Fixes the whole token / parent / probability sequence."""
+    rows = [ln.split() for ln in open(os.path.join(os.path.dirname(GOLDEN), "aaab_prim.txt"))
+            if ln.strip() and not ln.startswith("#")]
+    text = [int(x) for x in rows[0]]
+    want_freq = [int(x) for x in rows[1]]
+    start_state, start_token, max_size = (int(x) for x in rows[2])
+    draft = rows[3:]
+    sam = Sam.build(text)
+    sam.init_topk(2)
+    freq, tok, dst, prob = sam.topk()
+    assert freq.tolist() == want_freq
+    t, par, pr = sam.prim(start_state, start_token, max_size)
+    assert t.tolist() == [int(r[0]) for r in draft]
+    assert par.tolist() == [int(r[1]) for r in draft]
+    assert pr.tolist() == [np.float32(float(r[2])) for r in draft]
+    # a shorter draft is a prefix of the longer one
+    t3, par3, _ = sam.prim(start_state, start_token, 3)
+    assert t3.tolist() == t.tolist()[:3] and par3.tolist() == par.tolist()[:3]
+
+
 @pytest.mark.parametrize("seed", range(16))
 def test_prim_is_best_first_over_the_topk_tree(seed):
     rng = np.random.default_rng(500 + seed)
