@@ -65,9 +65,9 @@ def _gpu_schedule(w, sequences=None):
                 sizes=np.stack([c.cpu().numpy() for c in siz], axis=1))
 
 
-def _oracle_schedule(w, seqs):
-    """The checker on the chosen sequences (all steps)."""
-    from oracle.sam_oracle import Batch, Sam
+def _oracle_static(w):
+    """The checker's corpus automaton (None without a corpus)."""
+    from oracle.sam_oracle import Sam
     spec = w.spec
     t0 = time.time()
     static = None
@@ -75,6 +75,15 @@ def _oracle_schedule(w, seqs):
         static = Sam.build(w.corpus, progress=lambda done, total: _say(
             "%s: checker build %d/%d" % (spec.name, done, total)))
     _say("%s: checker built the corpus automaton in %.1f s" % (spec.name, time.time() - t0))
+    return static
+
+
+def _oracle_schedule(w, seqs, static=None):
+    """The checker on the chosen sequences (all steps)."""
+    from oracle.sam_oracle import Batch
+    spec = w.spec
+    if static is None:
+        static = _oracle_static(w)
     ob = Batch(static, w.corpus, [w.prompts[b] for b in seqs], spec.max_accept, spec.draft_len,
                spec.l_bias)
     S, nb, L = w.steps, len(seqs), spec.draft_len
@@ -106,9 +115,15 @@ def _compare(g, r, seqs, has_static=True):
 def _sampled(spec, n_check, has_static=True):
     w = make_workload(spec)
     _say("%s: workload generated (corpus %d tokens)" % (spec.name, spec.corpus_tokens))
-    g = _gpu_schedule(w)
+    # the checker builds its own corpus automaton on another host thread while the
+    # library builds and runs (both are foreign calls that release the interpreter lock)
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(1) as pool:
+        fut = pool.submit(_oracle_static, w)
+        g = _gpu_schedule(w)
+        static = fut.result()
     seqs = sorted(set(np.linspace(0, spec.batch - 1, n_check).astype(int).tolist()))
-    r = _oracle_schedule(w, seqs)
+    r = _oracle_schedule(w, seqs, static)
     _compare(g, r, seqs, has_static=has_static)
     T = spec.max_seq_len
     assert (g["sizes"][:, 0] == T).all()
@@ -137,9 +152,11 @@ def test_cfg5_shape_scaled_corpus():
     _sampled(CONFIGS["cfg5"].scaled(corpus_tokens=5_000_000), 16)
 
 
-@pytest.mark.skipif(os.environ.get("SAM_TEST_LARGE") != "1",
-                    reason="minutes of host time and >20 GB of host memory: set SAM_TEST_LARGE=1")
 def test_cfg3_full_corpus():
+    """Config 3 at full size: 100 M-token corpus (145 M states: state records and
+    transition table both beyond 4 GiB), 256 sequences, the whole schedule; 16
+    sequences replayed by the checker.  A few minutes of host time, about 40 GB of
+    host memory."""
     _sampled(CONFIGS["cfg3"], 16)
 
 
