@@ -11,7 +11,9 @@
 #include <string.h>
 #include <sys/mman.h>
 
+#include <atomic>
 #include <new>
+#include <thread>
 
 #include "../../include/sam.h"
 
@@ -27,6 +29,33 @@ void *huge_alloc(size_t bytes)
     void *p = aligned_alloc(kHuge, rounded);
     if (p) (void)madvise(p, rounded, MADV_HUGEPAGE);
     return p;
+}
+
+// Run fn(lo, hi) over [0, n) cut into one contiguous range per worker thread.  The
+// passes that use it (token check, table clear, the end-position pass, the link
+// records) touch every element once and independently; Build-SAM itself is
+// sequential and stays on the calling thread.
+template <class F>
+void parallel_ranges(uint64_t n, F fn)
+{
+    unsigned hw = std::thread::hardware_concurrency();
+    unsigned workers = hw < 1 ? 1 : (hw > 16 ? 16 : hw);
+    if (n < (1u << 20)) workers = 1;
+    if (workers == 1) { fn((uint64_t)0, n); return; }
+    std::vector<std::thread> pool;
+    const uint64_t per = (n + workers - 1) / workers;
+    try {
+        for (unsigned w = 1; w < workers; w++) {
+            const uint64_t lo = per * w, hi = lo + per < n ? lo + per : n;
+            if (lo < hi) pool.emplace_back([=] { fn(lo, hi); });
+        }
+    } catch (...) {
+        // no more threads to be had: the calling thread does what is left
+        const uint64_t done = per * (1 + pool.size());
+        if (done < n) fn(done, n);
+    }
+    fn((uint64_t)0, per < n ? per : n);
+    for (auto &t : pool) t.join();
 }
 }  // namespace
 
@@ -80,12 +109,23 @@ int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string
         err = "sam_build: need tokens != NULL, 1 <= n_tokens <= 2^31-2, vocab >= 1";
         return SAM_EINVAL;
     }
-    for (int64_t i = 0; i < n; i++)
-        if (tokens[i] < 0 || tokens[i] >= vocab_) {
+    {
+        std::atomic<int64_t> first_bad(n);
+        parallel_ranges((uint64_t)n, [&](uint64_t lo, uint64_t hi) {
+            for (uint64_t i = lo; i < hi; i++)
+                if (tokens[i] < 0 || tokens[i] >= vocab_) {
+                    int64_t seen = first_bad.load();
+                    while ((int64_t)i < seen && !first_bad.compare_exchange_weak(seen, (int64_t)i)) {}
+                    return;
+                }
+        });
+        const int64_t i = first_bad.load();
+        if (i < n) {
             err = "sam_build: corpus token " + std::to_string(tokens[i]) + " at position " +
                   std::to_string(i) + " is outside [0, vocab)";
             return SAM_ETOKEN;
         }
+    }
     n_tokens = n;
     vocab = vocab_;
     n_buckets = static_buckets_for(n);
@@ -113,7 +153,9 @@ int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string
         err = "sam_build: out of host memory for the transition table";
         return SAM_ENOMEM;
     }
-    memset(slots, 0xFF, n_slots * sizeof(Slot));
+    parallel_ranges(n_slots, [&](uint64_t lo, uint64_t hi) {
+        memset(slots + lo, 0xFF, (hi - lo) * sizeof(Slot));
+    });
 
     auto new_state = [&](uint32_t l, uint32_t lk, uint32_t ep) -> uint32_t {
         len.push_back(l);
@@ -185,11 +227,11 @@ int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string
     }
 
     // the device reads min_endpos(target) where the build kept the list chain
-    for (uint64_t j = 0; j < n_slots; j++) {
-        if (progress && (j & ((1ull << 27) - 1)) == 0)
-            progress("finalize", (int64_t)j, (int64_t)n_slots, user);
-        if (slots[j].state != kNil) slots[j].w = endpos[slots[j].dst];
-    }
+    if (progress) progress("finalize", 0, (int64_t)n_slots, user);
+    parallel_ranges(n_slots, [&](uint64_t lo, uint64_t hi) {
+        for (uint64_t j = lo; j < hi; j++)
+            if (slots[j].state != kNil) slots[j].w = endpos[slots[j].dst];
+    });
     for (int32_t t = 0; t < vocab; t++)
         if (root[t].dst) root[t].endpos = endpos[root[t].dst];
     head.release();
@@ -429,8 +471,10 @@ uint32_t HostSam::find(uint32_t state, uint32_t token) const
 void HostSam::make_linkrec(std::vector<LinkPair> &out) const
 {
     out.resize(n_states);
+    parallel_ranges(n_states, [&](uint64_t lo, uint64_t hi) {
+        for (uint64_t s = lo ? lo : 1; s < hi; s++) out[s] = LinkPair{link[s], len[link[s]]};
+    });
     out[0] = LinkPair{0, 0};
-    for (uint32_t s = 1; s < n_states; s++) out[s] = LinkPair{link[s], len[link[s]]};
 }
 
 void HostSam::release_build_only() { head.release(); }
