@@ -329,8 +329,10 @@ int sam_batch_status(const sam_batch *batch, uint32_t *status, void *hip_stream)
  * of the two token loops instead of the assembly one; bit 3 makes every later
  * sam_build size the corpus automaton's transition table at 4.5 GiB whatever the
  * corpus (about that much host and device memory), so that table offsets beyond
- * 32 bits are reached with a corpus that builds in a moment.  mode 0 restores
- * the defaults.  Results are identical in every mode.
+ * 32 bits are reached with a corpus that builds in a moment; bit 4 makes the
+ * step kernel of every later sam_batch_init run with its two prefetching waves,
+ * which otherwise join only for batches of 128 sequences or more.  mode 0
+ * restores the defaults.  Results are identical in every mode.
  */
 int sam_set_layout_override(int mode);
 

@@ -39,6 +39,7 @@ struct BatchView {
     int32_t   l_threshold;     // < 0: no auxiliary drafter
     int32_t   has_static;
     int32_t   no_asm;          // testing: 1 = the C++ token loops instead of the assembly
+    int32_t   scout;           // 1 = the step kernel runs with its two prefetching waves
     int32_t  *dyn_text;        // [batch, max_seq_len]
     void     *dyn_rec;         // [batch, max_states] records of the chosen layout
     void     *dyn_slots;       // [batch, dyn_buckets] buckets of 128 bytes

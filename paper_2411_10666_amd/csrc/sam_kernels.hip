@@ -1362,14 +1362,154 @@ __device__ __forceinline__ void emit_draft(const StaticView &S, const BatchView 
     }
 }
 
+// ---- scout waves: memory-level parallelism for the two walks -----------------
+//
+// A walk is one chain of dependent loads, so a sequence keeps one or two memory
+// requests in flight while the device could serve thousands.  What the chain will
+// touch is largely predictable, though: after a mismatch both walks fall back to
+// short suffixes of the text, i.e. to the states reached from the root by the
+// strings x[j..k] for start positions j shortly before the position k being fed.
+// A scout wave follows those strings for every start position at once, one
+// position per lane, a few steps deep, and throws the results away: all it does is
+// pull the records and buckets into the cache the walking wave reads through,
+// where the walk then finds them in a fraction of the time of a miss.  Nothing the
+// scouts read influences the result; they never write.
+
+constexpr int kScoutHistory = 4;    // start positions before the step's first token
+constexpr int kScoutDepth   = 6;    // transitions followed from each start position
+
+// Token of every start position, one per lane: lanes [0, H) hold the H tokens that
+// precede the step in the sequence's text, lanes [H, H + count) the step's tokens;
+// kNil where there is none (or one outside the vocabulary).
+__device__ __forceinline__ uint32_t scout_tokens(const int32_t *text, uint32_t n0, uint32_t tv,
+                                                 int count, uint32_t vocab, int lane)
+{
+    const int H = kScoutHistory;
+    const uint32_t row = (uint32_t)__shfl((int)tv, lane >= H ? lane - H : 0);
+    uint32_t t = kNil;
+    if (lane < H) {
+        const int64_t at = (int64_t)n0 - H + lane;
+        if (at >= 0) t = (uint32_t)text[at];
+    } else if (lane - H < count) {
+        t = row;
+    }
+    return t < vocab ? t : kNil;
+}
+
+// Corpus automaton.  A bucket is fetched by 8 lanes (one slot each, one request per
+// bucket, as in the walk), so the wave follows 8 start positions at a time and
+// kRounds batches of 8 per transition depth; all their loads are in flight together.
+__device__ __forceinline__ void scout_static(const StaticView &S, uint32_t tk, int n_starts, int lane)
+{
+    constexpr int kRounds = 3;                  // start positions 0 .. 23
+    const int g = lane >> 3, i = lane & 7;
+    uint32_t st[kRounds];
+    uint32_t acc = 0;
+#pragma unroll
+    for (int r = 0; r < kRounds; r++) {
+        const int j = g + 8 * r;
+        const uint32_t t0 = (uint32_t)__shfl((int)tk, j);
+        st[r] = 0;
+        if (j < n_starts && t0 != kNil) st[r] = reinterpret_cast<const uint2 *>(S.root)[t0].x;
+    }
+    for (int d = 1; d <= kScoutDepth; d++) {
+        uint2 rec[kRounds];
+        uint4 sl[kRounds];
+        uint32_t tt[kRounds];
+        bool on[kRounds];
+        bool any = false;
+#pragma unroll
+        for (int r = 0; r < kRounds; r++) {
+            const int j = g + 8 * r + d;
+            tt[r] = (uint32_t)__shfl((int)tk, j & 63);
+            on[r] = st[r] != 0 && st[r] < S.n_states && j < n_starts && tt[r] != kNil;
+            rec[r] = make_uint2(kNil, 0);
+            sl[r] = make_uint4(kNil, kNil, 0, 0);
+            if (on[r]) {
+                rec[r] = reinterpret_cast<const uint2 *>(S.linkrec + st[r])[0];      // itok, idst
+                const uint64_t b = bucket_of(hash_key(st[r], tt[r]), S.n_buckets);
+                sl[r] = reinterpret_cast<const uint4 *>(S.slots)[b * kBucketSlots + i];
+            }
+            any |= on[r];
+        }
+        if (!__any(any)) break;
+#pragma unroll
+        for (int r = 0; r < kRounds; r++) {
+            const bool hit = on[r] && sl[r].x == st[r] && sl[r].y == tt[r];
+            const uint32_t gm = (uint32_t)(__ballot(hit) >> (g * 8)) & 0xFFu;
+            const uint32_t from = (uint32_t)__shfl((int)sl[r].z, g * 8 + (gm ? __builtin_ctz(gm) : 0));
+            uint32_t nxt = 0;
+            if (on[r]) {
+                if (rec[r].x == tt[r]) nxt = rec[r].y;
+                else if (gm) nxt = from;
+            }
+            acc ^= sl[r].w;
+            st[r] = nxt;
+        }
+    }
+    asm volatile("" :: "v"(acc), "v"(st[0]), "v"(st[1]), "v"(st[2]));
+}
+
+// The same over a sequence's own automaton in the compact layout (16-byte records,
+// buckets of 16 slots of 8 bytes, fetched by 16 lanes: 4 start positions at a time).
+// The tables change under the scout's eyes (wave 1 is extending them), so every index
+// read from them is checked before it is used.
+__device__ __forceinline__ void scout_dynamic_compact(const DynSeq &D, uint32_t max_states,
+                                                      uint32_t tk, int n_starts, int lane)
+{
+    constexpr int kRounds = 5;                  // start positions 0 .. 19
+    const uint4 *rec_t = reinterpret_cast<const uint4 *>(D.rec);
+    const uint2 *slot_t = reinterpret_cast<const uint2 *>(D.slots);
+    const int g = lane >> 4, i = lane & 15;
+    uint32_t st[kRounds];                       // kNil: this start position is finished
+    uint32_t acc = 0;
+#pragma unroll
+    for (int r = 0; r < kRounds; r++) st[r] = 0;                // the root
+    for (int d = 0; d <= kScoutDepth; d++) {
+        uint4 rec[kRounds];
+        uint2 sl[kRounds];
+        uint32_t tt[kRounds];
+        bool on[kRounds];
+        bool any = false;
+#pragma unroll
+        for (int r = 0; r < kRounds; r++) {
+            const int j = g + 4 * r + d;
+            tt[r] = (uint32_t)__shfl((int)tk, j & 63);
+            on[r] = st[r] < max_states && j < n_starts && tt[r] != kNil;
+            rec[r] = make_uint4(0, 0, kNil, 0);
+            sl[r] = make_uint2(kNil, 0);
+            if (on[r]) {
+                rec[r] = rec_t[st[r]];
+                sl[r] = slot_t[(size_t)dyn_bucket(D, st[r], tt[r]) * 16 + i];
+            }
+            any |= on[r];
+        }
+        if (!__any(any)) break;
+#pragma unroll
+        for (int r = 0; r < kRounds; r++) {
+            const bool hit = on[r] && sl[r].x == ((st[r] << 17) | tt[r]);
+            const uint32_t gm = (uint32_t)(__ballot(hit) >> (g * 16)) & 0xFFFFu;
+            const uint32_t from = (uint32_t)__shfl((int)sl[r].y, g * 16 + (gm ? __builtin_ctz(gm) : 0));
+            uint32_t nxt = kNil;
+            if (on[r]) {
+                if (rec[r].z == tt[r]) nxt = rec[r].w & 0xFFFFu;
+                else if (gm) nxt = from & 0xFFFFu;
+            }
+            acc ^= rec[r].x;
+            st[r] = nxt;
+        }
+    }
+    asm volatile("" :: "v"(acc), "v"(st[0]), "v"(st[1]), "v"(st[2]), "v"(st[3]), "v"(st[4]));
+}
+
 }  // namespace
 
 // One workgroup (2 waves) per sequence.  kIngest: sequence b is fed
 // tokens[offsets[b] : offsets[b+1]) and nothing is written to the draft
 // outputs.  Otherwise: sequence b is fed the first counts[b] tokens of
 // tokens[b * max_accept ...], then source selection and draft gather.
-template <class L, bool kIngest, bool kAsm>
-__global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B,
+template <class L, bool kIngest, bool kAsm, bool kScout>
+__global__ __launch_bounds__(kScout ? 256 : 128) void sam_feed_kernel(StaticView S, BatchView B,
                                                         const int32_t *__restrict__ seq_map,
                                                         const int32_t *__restrict__ tokens,
                                                         const int64_t *__restrict__ offsets,
@@ -1384,6 +1524,12 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
     const int b = (kIngest && seq_map) ? seq_map[blockIdx.x] : (int)blockIdx.x;
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
+    static_assert(!(kIngest && kScout), "scouts belong to the step kernel");
+    if (kScout) {
+        // the arrival counter of the two walking waves (see the end of the kernel)
+        if (threadIdx.x == 0) sh[7] = 0;
+        __syncthreads();
+    }
 
     // Kernel arguments span three cache lines; named together here, they are all
     // requested before the first of them is waited for.
@@ -1423,6 +1569,22 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
     if ((int64_t)n0 + count > (int64_t)B.max_seq_len) { fault |= SAM_STATUS_CAPACITY_BIT; count = 0; }
     const uint32_t vocab = (uint32_t)B.vocab;
 
+    if (kScout && wave >= 2) {
+        // the step's scouts (waves 2 and 3): prefetch, then leave; the barrier below
+        // waits for the two walking waves only
+        if (count > 0) {
+            const DynSeq D = dyn_region<L>(B, b);
+            const uint32_t tk = scout_tokens(D.text, n0, first, (int)count, vocab, lane);
+            const int n_starts = kScoutHistory + (count < 64 - kScoutHistory ? (int)count : 64 - kScoutHistory);
+            if (wave == 2) {
+                if (B.has_static) scout_static(S, tk, n_starts, lane);
+            } else {
+                if (L::kSlots == 16) scout_dynamic_compact(D, B.max_states, tk, n_starts, lane);
+            }
+        }
+        return;
+    }
+
     if (wave == 0) {
         uint32_t s = lane_get(mv, 0), l = lane_get(mv, 1), e = lane_get(mv, 2);
         if (B.has_static) static_feed(S, tok, count, vocab, lane, s, l, e, fault, kAsm, !kIngest, first);
@@ -1445,14 +1607,23 @@ __global__ __launch_bounds__(128) void sam_feed_kernel(StaticView S, BatchView B
             }
         }
     }
-    __syncthreads();
-    // meta->n is read by both waves above, so it is written only after the barrier
-    if (wave == 1) {
-        if (lane == 0) meta->n = sh[5];
-        return;
+    if (!kScout) {
+        __syncthreads();
+        if (wave == 1) return;
+    } else {
+        // The step's workgroup also holds the scouts, which a barrier would wait for, and
+        // neither walking wave should wait for the other.  Each of the two counts itself
+        // in when its words above (and, for wave 1, its text stores) are written; the one
+        // that comes second sees both halves and finishes the step, the first one leaves.
+        uint32_t before = 0;
+        if (lane == 0)
+            before = __hip_atomic_fetch_add(&sh[7], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (uni(before) == 0u) return;
     }
+    // meta->n is read by both waves at the top, long before either gets here
     const uint32_t s1 = sh[0], l1 = sh[1], e1 = sh[2];
     if (lane == 0) {
+        meta->n = sh[5];
         meta->s1 = s1; meta->l1 = l1; meta->e1 = e1;
         if (sh[6]) atomicOr(B.status, sh[6]);
     }
@@ -1646,20 +1817,30 @@ hipError_t launch_feed(const StaticView &S, const BatchView &B, const int32_t *s
                        const int32_t *counts, int32_t *match_len, int32_t *draft,
                        int32_t *draft_len, int32_t *source, hipStream_t stream)
 {
-    const dim3 grid(n_seqs), block(128);
-#define SAM_LAUNCH_FEED(LAYOUT, INGEST, ASM)                                                   \
-    hipLaunchKernelGGL((sam_feed_kernel<LAYOUT, INGEST, ASM>), grid, block, 0, stream, S, B,   \
-                       seq_map, tokens, offsets, counts, match_len, draft, draft_len, source)
+    const bool scout = !offsets && B.scout;
+    const dim3 grid(n_seqs), block(scout ? 256 : 128);
+#define SAM_LAUNCH_FEED(LAYOUT, INGEST, ASM, SCOUT)                                            \
+    hipLaunchKernelGGL((sam_feed_kernel<LAYOUT, INGEST, ASM, SCOUT>), grid, block, 0, stream,  \
+                       S, B, seq_map, tokens, offsets, counts, match_len, draft, draft_len,    \
+                       source)
     const int which = (B.compact ? 4 : 0) | (offsets ? 2 : 0) | ((B.no_asm || (S.n_buckets >> 32)) ? 0 : 1);
     switch (which) {
-    case 7: SAM_LAUNCH_FEED(CompactDyn, true, true); break;
-    case 6: SAM_LAUNCH_FEED(CompactDyn, true, false); break;
-    case 5: SAM_LAUNCH_FEED(CompactDyn, false, true); break;
-    case 4: SAM_LAUNCH_FEED(CompactDyn, false, false); break;
-    case 3: SAM_LAUNCH_FEED(WideDyn, true, true); break;
-    case 2: SAM_LAUNCH_FEED(WideDyn, true, false); break;
-    case 1: SAM_LAUNCH_FEED(WideDyn, false, true); break;
-    default: SAM_LAUNCH_FEED(WideDyn, false, false); break;
+    case 7: SAM_LAUNCH_FEED(CompactDyn, true, true, false); break;
+    case 6: SAM_LAUNCH_FEED(CompactDyn, true, false, false); break;
+    case 5: if (scout) SAM_LAUNCH_FEED(CompactDyn, false, true, true);
+            else SAM_LAUNCH_FEED(CompactDyn, false, true, false);
+            break;
+    case 4: if (scout) SAM_LAUNCH_FEED(CompactDyn, false, false, true);
+            else SAM_LAUNCH_FEED(CompactDyn, false, false, false);
+            break;
+    case 3: SAM_LAUNCH_FEED(WideDyn, true, true, false); break;
+    case 2: SAM_LAUNCH_FEED(WideDyn, true, false, false); break;
+    case 1: if (scout) SAM_LAUNCH_FEED(WideDyn, false, true, true);
+            else SAM_LAUNCH_FEED(WideDyn, false, true, false);
+            break;
+    default: if (scout) SAM_LAUNCH_FEED(WideDyn, false, false, true);
+             else SAM_LAUNCH_FEED(WideDyn, false, false, false);
+             break;
     }
 #undef SAM_LAUNCH_FEED
     return hipGetLastError();

@@ -149,6 +149,34 @@ def test_static_table_beyond_4_gib():
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("mode", [16, 17, 18, 20])
+@pytest.mark.parametrize("seed,vocab,A", [(90, 2, 5), (91, 4, 30), (92, 300, 70), (93, 32000, 16)])
+def test_scout_waves_change_nothing(seed, vocab, A, mode):
+    """The step kernel with its two prefetching waves (testing mode bit 4; by default they
+    join at 128 sequences): rows shorter and longer than the scouts reach (64 lanes),
+    empty and very short prompts (less history than the scouts look back), every table
+    layout, both forms of the token loops.  The scouts only read, so every output must
+    be what it is without them."""
+    from paper_2411_10666_amd import binding as sam
+    B, T, L, steps = 12, 900, 9, 25
+    _say("scout waves seed=%d vocab=%d A=%d mode=%d" % (seed, vocab, A, mode))
+    corpus, prompts, acc, counts = _random_case(seed, vocab, 3000, B, T, A, L, steps)
+    prompts[0] = prompts[0][:0]
+    prompts[1] = prompts[1][:2]
+    used = np.array([len(p) for p in prompts])
+    for s_ in range(steps):                       # shorter prompts leave the counts valid
+        counts[s_] = np.minimum(counts[s_], T - used)
+        used += counts[s_]
+    sam.sam_set_layout_override(mode)
+    try:
+        g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L)
+    finally:
+        sam.sam_set_layout_override(0)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r)
+
+
 @pytest.mark.parametrize("mode", [4, 6])
 @pytest.mark.parametrize("seed,vocab", [(50, 2), (51, 5), (52, 300), (53, 32000)])
 def test_cxx_token_loops(seed, vocab, mode):
@@ -640,7 +668,8 @@ def test_random_cases_in_every_mode(block):
     """50 small random cases per block: vocabulary, batch, lengths, row and draft sizes
     drawn at random, tokens that repeat themselves, copy the corpus or copy the prompt,
     and the library mode (assembly or C++ token loops, compact or wide tables, normal
-    or tight slot tables) drawn at random too."""
+    or tight slot tables, with or without the step kernel's scout waves) drawn at random
+    too."""
     from paper_2411_10666_amd import binding as sam
     for seed in range(7000 + 50 * block, 7050 + 50 * block):
         rng = np.random.default_rng(seed)
@@ -648,7 +677,7 @@ def test_random_cases_in_every_mode(block):
         B, T = int(rng.integers(1, 40)), int(rng.integers(20, 1200))
         A, L = int(rng.integers(1, 20)), int(rng.integers(1, 40))
         ncorp = int(rng.integers(0, 4000))
-        mode = int(rng.choice([0, 0, 1, 2, 3, 4, 6]))
+        mode = int(rng.choice([0, 0, 1, 2, 3, 4, 6])) | (16 if rng.random() < 0.5 else 0)
         corpus = rng.integers(0, vocab, size=ncorp).astype(np.int32) if ncorp > 10 else None
         prompts = [rng.integers(0, vocab, size=int(rng.integers(0, T // 2 + 1))).astype(np.int32)
                    for _ in range(B)]
