@@ -67,6 +67,11 @@ typedef struct sam_batch  sam_batch;
 
 const char *sam_last_error(void);
 
+/* Digest of the source files this binary was compiled from (16 hex digits, set by the
+ * build script; "unknown" for a build that did not pass one).  Lets a loader refuse a
+ * binary that is older than the sources beside it. */
+const char *sam_build_id(void);
+
 /*
  * Build-SAM (Algorithm 2) over `corpus_tokens` on the host, then copy the
  * automaton to device memory as flat arrays: the corpus text, one

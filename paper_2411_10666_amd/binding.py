@@ -27,7 +27,7 @@ EXPORTS = [
     "sam_batch_reset", "sam_set_progress_callback",
     "sam_batch_set_threshold", "sam_corpus_build_topk", "sam_corpus_export_topk",
     "sam_batch_tree_draft", "sam_corpus_save", "sam_corpus_load", "sam_corpus_load_host_only",
-    "sam_batch_replay", "sam_membench", "sam_batch_init_noalloc",
+    "sam_batch_replay", "sam_membench", "sam_batch_init_noalloc", "sam_build_id",
 ]
 
 
@@ -47,11 +47,19 @@ def _load():
     import torch  # noqa: F401
     path = _build.LIB
     if not os.path.exists(path):
-        # nothing built yet: build once; a stale library is the caller's business
-        _build.build()
+        _build.build()          # nothing built yet: build once
     L = C.CDLL(path)
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     L.sam_last_error.restype = C.c_char_p
+    # a library older than the sources beside it must not be what gets tested or timed
+    built_from = None
+    if hasattr(L, "sam_build_id"):
+        L.sam_build_id.restype = C.c_char_p
+        built_from = L.sam_build_id().decode()
+    if path == os.path.join(_build.HERE, "libsam_hip.so") and built_from != _build.source_digest():
+        raise ImportError("%s was built from other sources (%s) than those in %s (%s): run "
+                          "`python -m paper_2411_10666_amd.build`"
+                          % (path, built_from, _build.CSRC, _build.source_digest()))
     L.sam_build.argtypes = [vp, i64, i32, C.POINTER(vp)]
     L.sam_build_host_only.argtypes = [vp, i64, i32, C.POINTER(vp)]
     L.sam_corpus_info.argtypes = [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
@@ -81,7 +89,7 @@ def _load():
     L.sam_batch_free.argtypes = [vp]
     L.sam_batch_free.restype = None
     for name in EXPORTS:
-        if name not in ("sam_last_error", "sam_corpus_free", "sam_batch_free"):
+        if name not in ("sam_last_error", "sam_corpus_free", "sam_batch_free", "sam_build_id"):
             getattr(L, name).restype = C.c_int
     return L
 

@@ -17,20 +17,26 @@ HIPCC_FLAGS = [
 ]
 
 
-def is_stale() -> bool:
-    if not os.path.exists(LIB):
-        return True
-    t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(os.path.join(CSRC, f)) > t for f in SOURCES + HEADERS)
+def source_digest() -> str:
+    """Digest of every source and header the library is compiled from.  It is compiled
+    into the library (sam_build_id) so that a loaded binary can be told from one that
+    is older than the sources beside it, whatever the file times say."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in SOURCES + HEADERS:
+        with open(os.path.join(CSRC, f), "rb") as fh:
+            h.update(f.encode() + b"\0" + fh.read())
+    return h.hexdigest()[:16]
 
 
 def build(verbose: bool = False) -> str:
     """Always recompiles; returns the path of the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
+    build_id = '-DSAM_BUILD_ID="%s"' % source_digest()
     for src in SOURCES:
         obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-        cmd = [hipcc] + HIPCC_FLAGS + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc] + HIPCC_FLAGS + [build_id, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)

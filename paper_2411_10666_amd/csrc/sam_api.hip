@@ -114,6 +114,11 @@ extern "C" {
 
 const char *sam_last_error(void) { return g_err.c_str(); }
 
+#ifndef SAM_BUILD_ID
+#define SAM_BUILD_ID "unknown"
+#endif
+const char *sam_build_id(void) { return SAM_BUILD_ID; }
+
 static void corpus_release_device(sam_corpus *c)
 {
     if (c->d_text) (void)hipFree(c->d_text);

@@ -633,7 +633,10 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
         "s_add_u32 %[n], %[n], 1\n\t"
         "s_mov_b32 s87, %[last]\n\t"
         "s_mov_b32 %[last], s82\n\t"
+        // guard: suffix-link and list chains take fewer than n_states moves in all, sweeps
+        // past full buckets fewer than n_buckets
         "s_add_u32 s86, %[ns], 4\n\t"
+        "s_add_u32 s86, s86, %[nb]\n\t"
         "s_cmp_eq_u32 %[P], -1\n\t"
         "s_cbranch_scc0 L_walk_%=\n\t"
         // the sequence's very first token: last is the root, which now has (t -> cur)

@@ -168,3 +168,10 @@ def test_load_refuses_damaged_files(tmp_path):
     expect_refused(bad_slot)
     with pytest.raises(sam.SamError):
         sam.sam_corpus_load_host_only(str(tmp_path / "missing.sam"))
+
+
+def test_loaded_library_was_built_from_the_sources_in_the_tree():
+    from paper_2411_10666_amd import build
+    lib = ctypes.CDLL(sam.LIB_PATH)
+    lib.sam_build_id.restype = ctypes.c_char_p
+    assert lib.sam_build_id().decode() == build.source_digest()

@@ -149,6 +149,45 @@ def test_static_table_beyond_4_gib():
     torch.cuda.empty_cache()
 
 
+def test_multi_document_corpus_with_separators():
+    """Section 3.1: the documents of a corpus are joined by a separator token into one
+    string and one automaton.  40 documents joined by token vocab-1; sequences copy
+    stretches that run across a separator, so matches and drafts cross document ends
+    (nothing is special-cased: the separator is a token like any other)."""
+    rng = np.random.default_rng(4242)
+    vocab, sep = 500, 499
+    docs = [rng.integers(0, sep, size=int(rng.integers(20, 400))).astype(np.int32) for _ in range(40)]
+    corpus = np.concatenate([np.concatenate([d, [sep]]).astype(np.int32) for d in docs])
+    sep_at = np.flatnonzero(corpus == sep)
+    B, T, A, L, steps = 20, 600, 6, 12, 60
+    prompts, acc, counts = [], np.zeros((steps, B, A), np.int32), np.zeros((steps, B), np.int32)
+    for b in range(B):
+        x = rng.integers(0, sep, size=T).astype(np.int32)
+        for _ in range(12):                      # stretches that straddle a separator
+            at = int(sep_at[rng.integers(0, len(sep_at) - 1)])
+            lo, hi = max(0, at - int(rng.integers(2, 15))), min(len(corpus), at + int(rng.integers(2, 15)))
+            pos = int(rng.integers(0, T - (hi - lo)))
+            x[pos:pos + hi - lo] = corpus[lo:hi]
+        pl = int(rng.integers(50, 200))
+        prompts.append(x[:pl])
+        used = pl
+        for s_ in range(steps):
+            c = min(int(rng.integers(0, A + 1)), T - used)
+            counts[s_, b] = c
+            acc[s_, b, :c] = x[used:used + c]
+            used += c
+    _say("multi-document corpus: %d documents, %d tokens" % (len(docs), len(corpus)))
+    g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r)
+    crossing_drafts = sum(int(((x["draft"] == sep).any(axis=1) & (x["source"] == 2)).sum()) for x in r)
+    assert crossing_drafts > 20, crossing_drafts
+    # a match that itself contains a separator: longer than the distance back to it
+    long_static = sum(int(((x["source"] == 2) & (x["match_len"] >= 8)).sum()) for x in r)
+    assert long_static > 20, long_static
+
+
 @pytest.mark.parametrize("mode", [16, 17, 18, 20])
 @pytest.mark.parametrize("seed,vocab,A", [(90, 2, 5), (91, 4, 30), (92, 300, 70), (93, 32000, 16)])
 def test_scout_waves_change_nothing(seed, vocab, A, mode):
