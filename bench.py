@@ -230,10 +230,29 @@ def gpu_leg(w, steps, warmup, tree=None, replay=True, before_timing=None):
             sam.sam_batch_tree_draft(batch, max_size, tt, tp, tpr, ts, stream)
         e1.record(stream)
         torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / calls
-        entries = int(ts.sum().item())
+        ms_warm = e0.elapsed_time(e1) / calls
+        # The figure that counts: every call on cursor states it has not seen (one step of
+        # the schedule between two calls moves every sequence on), so the table rows come
+        # from HBM, not from the caches a repeated call would find them in.
+        fb, _ = new_batch()
+        n_fresh = min(200, S)
+        evs = []
+        for i in range(n_fresh):
+            run(fb, i, i + 1)
+            a = torch.cuda.Event(enable_timing=True)
+            b_ = torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            sam.sam_batch_tree_draft(fb, max_size, tt, tp, tpr, ts, stream)
+            b_.record(stream)
+            evs.append((a, b_))
+        torch.cuda.synchronize()
+        ms = sum(a.elapsed_time(b_) for a, b_ in evs) / n_fresh
+        entries = int(ts.sum().item())           # of the last call; drafts nearly always fill up
+        # dependent-load floor: the pops of one draft are a chain of table reads
         tree_out = {"k": k, "max_size": max_size, "ms_per_call": ms,
+                    "ms_per_call_same_states_repeated": ms_warm, "calls": n_fresh,
                     "entries_per_call": entries, "entries_per_s": entries / (ms * 1e-3),
+                    "us_per_entry_of_one_draft": ms * 1e3 / max(1.0, entries / B),
                     "topk_build_s": topk_s,
                     # per entry: one k x 12 B table read and 12 B of output
                     "algo_gbps": entries * (12.0 * k + 12.0) / (ms * 1e-3) / 1e9}

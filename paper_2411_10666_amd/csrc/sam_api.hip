@@ -151,17 +151,21 @@ static int corpus_upload(sam_corpus *c)
     HIP_TRY(hipMemcpy(c->d_root, h.root.data(), b_root, hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(c->d_slots, h.slots, b_slots, hipMemcpyHostToDevice));
     {
-        // link pairs -> 32-byte state records with one transition inline
-        void *d_pairs = nullptr;
+        // link pairs -> 32-byte state records with two transitions inline
+        void *d_pairs = nullptr, *d_wide = nullptr;
         const size_t b_pairs = (size_t)h.n_states * sizeof(LinkPair);
+        const size_t b_wide = ((size_t)h.n_states + 31) / 32 * sizeof(uint32_t);
         HIP_TRY(hipMalloc(&d_pairs, b_pairs));
-        hipError_t e = hipMemcpy(d_pairs, lr.data(), b_pairs, hipMemcpyHostToDevice);
+        hipError_t e = hipMalloc(&d_wide, b_wide);
+        if (e == hipSuccess) e = hipMemset(d_wide, 0, b_wide);
+        if (e == hipSuccess) e = hipMemcpy(d_pairs, lr.data(), b_pairs, hipMemcpyHostToDevice);
         if (e == hipSuccess)
-            e = launch_staterec((const LinkPair *)d_pairs, (const Slot *)c->d_slots,
-                                (LinkRec *)c->d_linkrec, h.n_states,
-                                h.n_buckets * kBucketSlots, nullptr);
+            e = launch_staterec((const LinkPair *)d_pairs, (Slot *)c->d_slots, (RootEnt *)c->d_root,
+                                (LinkRec *)c->d_linkrec, (uint32_t *)d_wide, h.n_states,
+                                h.n_buckets * kBucketSlots, (uint32_t)h.vocab, nullptr);
         if (e == hipSuccess) e = hipDeviceSynchronize();
         (void)hipFree(d_pairs);
+        if (d_wide) (void)hipFree(d_wide);
         if (e != hipSuccess) return fail_hip("sam_build: state records", e);
     }
     c->view.text = (const int32_t *)c->d_text;

@@ -54,9 +54,12 @@ hipError_t launch_feed(const StaticView &S, const BatchView &B, const int32_t *s
                        const int32_t *counts, int32_t *match_len, int32_t *draft,
                        int32_t *draft_len, int32_t *source, hipStream_t stream);
 // A whole schedule of n_steps steps in one launch (rows [step, sequence] of every array).
-// linkrec[s] from the link pairs and the (already uploaded) slot table
-hipError_t launch_staterec(const LinkPair *pairs, const Slot *slots, LinkRec *linkrec,
-                           uint32_t n_states, uint64_t n_slots, hipStream_t stream);
+// linkrec[s] from the link pairs and the (already uploaded) slot and root tables, whose end
+// positions receive the wide flag of their targets.  wide: (n_states + 31) / 32 words of
+// scratch, zeroed by the caller.
+hipError_t launch_staterec(const LinkPair *pairs, Slot *slots, RootEnt *root, LinkRec *linkrec,
+                           uint32_t *wide, uint32_t n_states, uint64_t n_slots, uint32_t vocab,
+                           hipStream_t stream);
 hipError_t launch_replay(const StaticView &S, const BatchView &B, int n_steps,
                          const int32_t *accepted, const int32_t *counts, int32_t *match_len,
                          int32_t *draft, int32_t *draft_len, int32_t *source, hipStream_t stream);

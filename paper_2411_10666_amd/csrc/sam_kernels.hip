@@ -68,7 +68,8 @@ __device__ __forceinline__ void order_memory()
 
 // ---- static automaton: Transfer (Algorithm 1) -----------------------------
 
-// Feed one token.  (s, l) is the cursor, e = min_endpos(s).
+// Feed one token.  (s, l) is the cursor, e = min_endpos(s) with the wide flag of s
+// in bit 31 (a state is wide if it has transitions beyond the two in its record).
 __device__ __forceinline__ void static_transfer(const StaticView &S, uint32_t t, int lane,
                                                 uint32_t &s, uint32_t &l, uint32_t &e,
                                                 uint32_t &fault)
@@ -85,39 +86,51 @@ __device__ __forceinline__ void static_transfer(const StaticView &S, uint32_t t,
             else   { l = 0; e = 0; }
             return;
         }
-        // fetch the suffix-link record together with the bucket: it is only
-        // needed on a miss, but then it is already here
+        // the record answers for a state with at most two transitions; a wide state's
+        // bucket is requested together with it
+        const bool wide = (e & kWideBit) != 0;
         const LinkRec lr = S.linkrec[s];
-        if (uni(lr.itok) == t) {            // the transition the record repeats
+        uint64_t b = 0;
+        uint4 sl = make_uint4(kNil, kNil, 0, 0);
+        if (wide) {
+            b = bucket_of(hash_key(s, t), S.n_buckets);
+            sl = reinterpret_cast<const uint4 *>(S.slots)[b * kBucketSlots + (lane & 7)];
+        }
+        if (uni(lr.itok) == t) {
             s = uni(lr.idst); e = uni(lr.iendpos); l += 1;
             return;
         }
-        uint64_t b = bucket_of(hash_key(s, t), S.n_buckets);
-        uint4 sl = reinterpret_cast<const uint4 *>(S.slots)[b * kBucketSlots + (lane & 7)];
-        uint32_t mh = (uint32_t)__ballot(sl.x == s && sl.y == t) & 0xFFu;
-        uint32_t me = (uint32_t)__ballot(sl.x == kNil) & 0xFFu;
+        if (uni(lr.itok2) == t) {
+            s = uni(lr.idst2); e = uni(lr.iendpos2); l += 1;
+            return;
+        }
         uint32_t nlink = uni(lr.link), nlen = uni(lr.lenlink);
         pin_s(nlink);
-        pin_s(mh);
         bool hit = false;
-        for (uint64_t left = S.n_buckets; left; left--) {
-            if (mh) {
-                const int j = __builtin_ctz(mh);
-                s = lane_get(sl.z, j);
-                e = lane_get(sl.w, j);
-                l += 1;
-                hit = true;
-                break;
+        if (wide) {
+            uint32_t mh = (uint32_t)__ballot(sl.x == s && sl.y == t) & 0xFFu;
+            uint32_t me = (uint32_t)__ballot(sl.x == kNil) & 0xFFu;
+            pin_s(mh);
+            for (uint64_t left = S.n_buckets; left; left--) {
+                if (mh) {
+                    const int j = __builtin_ctz(mh);
+                    s = lane_get(sl.z, j);
+                    e = lane_get(sl.w, j);
+                    l += 1;
+                    hit = true;
+                    break;
+                }
+                if (me) break;
+                b = (b + 1 == S.n_buckets) ? 0 : b + 1;
+                sl = reinterpret_cast<const uint4 *>(S.slots)[b * kBucketSlots + (lane & 7)];
+                mh = (uint32_t)__ballot(sl.x == s && sl.y == t) & 0xFFu;
+                me = (uint32_t)__ballot(sl.x == kNil) & 0xFFu;
             }
-            if (me) break;
-            b = (b + 1 == S.n_buckets) ? 0 : b + 1;
-            sl = reinterpret_cast<const uint4 *>(S.slots)[b * kBucketSlots + (lane & 7)];
-            mh = (uint32_t)__ballot(sl.x == s && sl.y == t) & 0xFFu;
-            me = (uint32_t)__ballot(sl.x == kNil) & 0xFFu;
         }
         if (hit) return;
         s = nlink;
-        l = nlen;
+        l = nlen & ~kWideBit;
+        e = nlen & kWideBit;
     }
 }
 
@@ -1044,7 +1057,7 @@ __device__ __forceinline__ void dyn_feed_compact(u32x4 rrec, u32x4 rslt, uint32_
 //   s64 t   s65 t * c2   s66 link-hop guard   s67 bucket-sweep guard
 //   s68:69 s70:71 addresses / compare results   s72 hash   s73 bucket
 //   s74 hit mask   s75 empty mask   s76:77 compare result   s78 s79 scratch
-//   v41 zero   v42:45 slot {state, token, dst, endpos}   s88..s92 state record   v46:47 root entry
+//   v41 zero   v42:45 slot {state, token, dst, endpos}   s88..s95 state record   v46:47 root entry
 __device__ __forceinline__ void static_feed_asm(uint32_t slots_lo, uint32_t slots_hi,
                                                 uint32_t lr_lo, uint32_t lr_hi, uint32_t root_lo,
                                                 uint32_t root_hi, uint32_t nb, uint32_t m,
@@ -1067,15 +1080,18 @@ __device__ __forceinline__ void static_feed_asm(uint32_t slots_lo, uint32_t slot
         "s_cbranch_scc1 L_scorrupt_%=\n\t"
         "s_cmp_eq_u32 %[st], 0\n\t"
         "s_cbranch_scc1 L_sroot_%=\n\t"
-        // the state's record {itok, idst, iendpos, link, lenlink}, in flight together
-        // with the bucket.  It comes through the scalar cache (the table is read-only),
-        // which has its own counter: vector loads return in order, so a record behind
-        // a bucket in the same queue could not arrive before it
+        // the state's record {itok, idst, iendpos, itok2, idst2, iendpos2, link, lenlink}.
+        // It comes through the scalar cache (the table is read-only), which has its own
+        // counter: vector loads return in order, so a record behind a bucket in the same
+        // queue could not arrive before it.  Bit 31 of e says whether the state is wide;
+        // if not, its record holds all its transitions and no bucket is requested.
         "s_lshl_b32 s68, %[st], 5\n\t"
         "s_lshr_b32 s69, %[st], 27\n\t"
         "s_add_u32 s68, s68, %[lr_lo]\n\t"
         "s_addc_u32 s69, s69, %[lr_hi]\n\t"
         "s_load_dwordx8 s[88:95], s[68:69], 0x0\n\t"
+        "s_bitcmp1_b32 %[e], 31\n\t"
+        "s_cbranch_scc0 L_srec_%=\n\t"
         "s_mul_i32 s72, %[st], 0x9e3779b1\n\t"
         "s_add_u32 s72, s72, s65\n\t"
         "s_lshr_b32 s79, s72, 15\n\t"
@@ -1099,7 +1115,16 @@ __device__ __forceinline__ void static_feed_asm(uint32_t slots_lo, uint32_t slot
         "s_waitcnt lgkmcnt(0)\n\t"
         "s_cmp_eq_u32 s88, s64\n\t"
         "s_cbranch_scc1 L_sinline_%=\n\t"
+        "s_cmp_eq_u32 s91, s64\n\t"
+        "s_cbranch_scc1 L_sinline2_%=\n\t"
         "s_branch L_swait_%=\n"
+        "L_srec_%=:\n\t"
+        "s_waitcnt lgkmcnt(0)\n\t"
+        "s_cmp_eq_u32 s88, s64\n\t"
+        "s_cbranch_scc1 L_sinline_%=\n\t"
+        "s_cmp_eq_u32 s91, s64\n\t"
+        "s_cbranch_scc1 L_sinline2_%=\n\t"
+        "s_branch L_smiss_%=\n"
         "L_sload_%=:\n\t"
         "s_lshl_b32 s70, s73, 7\n\t"
         "s_lshr_b32 s71, s73, 25\n\t"
@@ -1135,9 +1160,15 @@ __device__ __forceinline__ void static_feed_asm(uint32_t slots_lo, uint32_t slot
         "s_mov_b32 %[st], s89\n\t"
         "s_mov_b32 %[e], s90\n\t"
         "s_branch L_sdone_%=\n"
+        "L_sinline2_%=:\n\t"
+        "s_add_u32 %[l], %[l], 1\n\t"
+        "s_mov_b32 %[st], s92\n\t"
+        "s_mov_b32 %[e], s93\n\t"
+        "s_branch L_sdone_%=\n"
         "L_smiss_%=:\n\t"
-        "s_mov_b32 %[st], s91\n\t"              // follow the suffix link
-        "s_mov_b32 %[l], s92\n\t"
+        "s_mov_b32 %[st], s94\n\t"              // follow the suffix link
+        "s_and_b32 %[l], s95, 0x7fffffff\n\t"
+        "s_and_b32 %[e], s95, 0x80000000\n\t"   // its wide flag; its end position is not needed
         "s_branch L_stry_%=\n"
         "L_sroot_%=:\n\t"
         "s_lshl_b32 s68, s64, 3\n\t"
@@ -1345,7 +1376,7 @@ __device__ __forceinline__ void emit_draft(const StaticView &S, const BatchView 
 {
     const bool use_static = B.has_static && ((int64_t)l1 > (int64_t)l2 + (int64_t)B.l_bias);
     const uint32_t ml = use_static ? l1 : l2;
-    const uint32_t p = use_static ? e1 : e2;
+    const uint32_t p = use_static ? (e1 & ~kWideBit) : e2;
     const int32_t *T = use_static ? S.text : B.dyn_text + (size_t)b * B.max_seq_len;
     const uint32_t Tn = use_static ? S.n_tokens : n1;
     const int Ld = B.draft_len;
@@ -1372,31 +1403,24 @@ __device__ __forceinline__ void emit_draft(const StaticView &S, const BatchView 
 // touch is largely predictable, though: after a mismatch both walks fall back to
 // short suffixes of the text, i.e. to the states reached from the root by the
 // strings x[j..k] for start positions j shortly before the position k being fed.
-// A scout wave follows those strings for every start position at once, one
-// position per lane, a few steps deep, and throws the results away: all it does is
+// A scout wave follows those strings for the start positions inside the step's row
+// of tokens, several at a time, a few steps deep, and throws the results away: all it does is
 // pull the records and buckets into the cache the walking wave reads through,
 // where the walk then finds them in a fraction of the time of a miss.  Nothing the
 // scouts read influences the result; they never write.
 
-constexpr int kScoutHistory = 4;    // start positions before the step's first token
-constexpr int kScoutDepth   = 6;    // transitions followed from each start position
+// How far each start position is followed.  Measured on the benchmark shapes: three
+// transitions deep is the best trade between what the walks then find in the cache
+// and what the scouts' own requests cost them in the queues they share; start
+// positions before the step's first token (which need a dependent read of the
+// sequence's text before the scouts can start) cost more than they bring.
+constexpr int kScoutDepth = 3;
 
-// Token of every start position, one per lane: lanes [0, H) hold the H tokens that
-// precede the step in the sequence's text, lanes [H, H + count) the step's tokens;
-// kNil where there is none (or one outside the vocabulary).
-__device__ __forceinline__ uint32_t scout_tokens(const int32_t *text, uint32_t n0, uint32_t tv,
-                                                 int count, uint32_t vocab, int lane)
+// Token of every start position, one per lane: lane j holds the step's token j, kNil
+// beyond the row's end (or for a token outside the vocabulary).
+__device__ __forceinline__ uint32_t scout_tokens(uint32_t tv, int count, uint32_t vocab, int lane)
 {
-    const int H = kScoutHistory;
-    const uint32_t row = (uint32_t)__shfl((int)tv, lane >= H ? lane - H : 0);
-    uint32_t t = kNil;
-    if (lane < H) {
-        const int64_t at = (int64_t)n0 - H + lane;
-        if (at >= 0) t = (uint32_t)text[at];
-    } else if (lane - H < count) {
-        t = row;
-    }
-    return t < vocab ? t : kNil;
+    return (lane < count && tv < vocab) ? tv : kNil;
 }
 
 // Corpus automaton.  A bucket is fetched by 8 lanes (one slot each, one request per
@@ -1406,17 +1430,20 @@ __device__ __forceinline__ void scout_static(const StaticView &S, uint32_t tk, i
 {
     constexpr int kRounds = 3;                  // start positions 0 .. 23
     const int g = lane >> 3, i = lane & 7;
-    uint32_t st[kRounds];
+    uint32_t st[kRounds], ep[kRounds];          // state, its end position word (wide flag in bit 31)
     uint32_t acc = 0;
 #pragma unroll
     for (int r = 0; r < kRounds; r++) {
         const int j = g + 8 * r;
         const uint32_t t0 = (uint32_t)__shfl((int)tk, j);
-        st[r] = 0;
-        if (j < n_starts && t0 != kNil) st[r] = reinterpret_cast<const uint2 *>(S.root)[t0].x;
+        st[r] = 0; ep[r] = 0;
+        if (j < n_starts && t0 != kNil) {
+            const uint2 re = reinterpret_cast<const uint2 *>(S.root)[t0];
+            st[r] = re.x; ep[r] = re.y;
+        }
     }
     for (int d = 1; d <= kScoutDepth; d++) {
-        uint2 rec[kRounds];
+        uint4 ra[kRounds], rb[kRounds];
         uint4 sl[kRounds];
         uint32_t tt[kRounds];
         bool on[kRounds];
@@ -1426,12 +1453,17 @@ __device__ __forceinline__ void scout_static(const StaticView &S, uint32_t tk, i
             const int j = g + 8 * r + d;
             tt[r] = (uint32_t)__shfl((int)tk, j & 63);
             on[r] = st[r] != 0 && st[r] < S.n_states && j < n_starts && tt[r] != kNil;
-            rec[r] = make_uint2(kNil, 0);
+            ra[r] = make_uint4(kNil, 0, 0, kNil);
+            rb[r] = make_uint4(0, 0, 0, 0);
             sl[r] = make_uint4(kNil, kNil, 0, 0);
             if (on[r]) {
-                rec[r] = reinterpret_cast<const uint2 *>(S.linkrec + st[r])[0];      // itok, idst
-                const uint64_t b = bucket_of(hash_key(st[r], tt[r]), S.n_buckets);
-                sl[r] = reinterpret_cast<const uint4 *>(S.slots)[b * kBucketSlots + i];
+                const uint4 *rec = reinterpret_cast<const uint4 *>(S.linkrec + st[r]);
+                ra[r] = rec[0];                  // itok, idst, iendpos, itok2
+                rb[r] = rec[1];                  // idst2, iendpos2, link, lenlink
+                if (ep[r] & kWideBit) {
+                    const uint64_t b = bucket_of(hash_key(st[r], tt[r]), S.n_buckets);
+                    sl[r] = reinterpret_cast<const uint4 *>(S.slots)[b * kBucketSlots + i];
+                }
             }
             any |= on[r];
         }
@@ -1440,14 +1472,17 @@ __device__ __forceinline__ void scout_static(const StaticView &S, uint32_t tk, i
         for (int r = 0; r < kRounds; r++) {
             const bool hit = on[r] && sl[r].x == st[r] && sl[r].y == tt[r];
             const uint32_t gm = (uint32_t)(__ballot(hit) >> (g * 8)) & 0xFFu;
-            const uint32_t from = (uint32_t)__shfl((int)sl[r].z, g * 8 + (gm ? __builtin_ctz(gm) : 0));
-            uint32_t nxt = 0;
+            const int from = g * 8 + (gm ? __builtin_ctz(gm) : 0);
+            const uint32_t sd = (uint32_t)__shfl((int)sl[r].z, from);
+            const uint32_t se = (uint32_t)__shfl((int)sl[r].w, from);
+            uint32_t nxt = 0, nep = 0;
             if (on[r]) {
-                if (rec[r].x == tt[r]) nxt = rec[r].y;
-                else if (gm) nxt = from;
+                if (ra[r].x == tt[r]) { nxt = ra[r].y; nep = ra[r].z; }
+                else if (ra[r].w == tt[r]) { nxt = rb[r].x; nep = rb[r].y; }
+                else if (gm) { nxt = sd; nep = se; }
             }
-            acc ^= sl[r].w;
-            st[r] = nxt;
+            acc ^= rb[r].w;
+            st[r] = nxt; ep[r] = nep;
         }
     }
     asm volatile("" :: "v"(acc), "v"(st[0]), "v"(st[1]), "v"(st[2]));
@@ -1577,8 +1612,8 @@ __global__ __launch_bounds__(kScout ? 256 : 128) void sam_feed_kernel(StaticView
         // waits for the two walking waves only
         if (count > 0) {
             const DynSeq D = dyn_region<L>(B, b);
-            const uint32_t tk = scout_tokens(D.text, n0, first, (int)count, vocab, lane);
-            const int n_starts = kScoutHistory + (count < 64 - kScoutHistory ? (int)count : 64 - kScoutHistory);
+            const uint32_t tk = scout_tokens(first, (int)count, vocab, lane);
+            const int n_starts = count < 64 ? (int)count : 64;
             if (wave == 2) {
                 if (B.has_static) scout_static(S, tk, n_starts, lane);
             } else {
@@ -1597,7 +1632,27 @@ __global__ __launch_bounds__(kScout ? 256 : 128) void sam_feed_kernel(StaticView
         DynCursor<L> c;
         cursor_from_lanes<L>(mv, c);
         c.rec_bytes = (uint32_t)B.max_states * 16u;
+        // The first token of a step finds nothing of the sequence's tables in the caches,
+        // and its lookups come one after the other: the bucket at P, then record and
+        // bucket one suffix link up, then at the root.  Their addresses are all known
+        // now, so they are requested here at once and not waited for (the value is only
+        // named again after the token loop); the loop's own requests then meet them on
+        // the way or in the cache.
+        uint32_t warm = 0;
+        if (kScout && L::kSlots == 16 && count > 0 && c.P != kNil) {
+            const uint32_t t0 = lane_get(first, 0);
+            if (t0 < vocab) {
+                const uint32_t up = c.RP.link == kNil ? 0u : c.RP.link;
+                const uint32_t at = lane < 16 ? c.P : (lane < 32 ? up : 0u);
+                const uint2 *slots = reinterpret_cast<const uint2 *>(D.slots);
+                if (lane < 48 && at < B.max_states)
+                    warm = slots[(size_t)dyn_bucket(D, at, t0) * 16 + (lane & 15)].y;
+                else if (lane < 50 && up < B.max_states)
+                    warm = reinterpret_cast<const uint4 *>(D.rec)[lane == 48 ? up : 0u].x;
+            }
+        }
         dyn_feed<L>(D, tok, count, vocab, lane, c, fault, kAsm, !kIngest, first);
+        asm volatile("" :: "v"(warm));
         if (c.n != n0) flush_last<L>(D, c, lane);
         if (lane == 0) {
             sh[3] = c.P == kNil ? 0u : c.RP.len;
@@ -1621,7 +1676,19 @@ __global__ __launch_bounds__(kScout ? 256 : 128) void sam_feed_kernel(StaticView
         uint32_t before = 0;
         if (lane == 0)
             before = __hip_atomic_fetch_add(&sh[7], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
-        if (uni(before) == 0u) return;
+        if (uni(before) == 0u) {
+            // first to arrive: nothing left to do -- except, for the static walk, to ask
+            // for the corpus text its draft would be read from, so that the wave that
+            // finishes the step finds it on the way
+            if (wave == 0 && B.has_static && sh[1] > 0) {
+                const uint32_t at = (sh[2] & ~kWideBit) + 32u * (uint32_t)lane;
+                if (32 * lane < B.draft_len + 32 && at < S.n_tokens) {
+                    const int32_t v = S.text[at];
+                    asm volatile("" :: "v"(v));
+                }
+            }
+            return;
+        }
     }
     // meta->n is read by both waves at the top, long before either gets here
     const uint32_t s1 = sh[0], l1 = sh[1], e1 = sh[2];
@@ -1771,40 +1838,109 @@ __global__ void sam_debug_kernel(BatchView B, int32_t *s1, int32_t *l1, int32_t 
 }
 
 // ---- the static state records, built once per corpus ------------------------
+//
+// While the passes below run, the fields of a record hold intermediate values:
+// word 0 the number of transitions seen, words 2-3 and 4-5 two 64-bit keys.
+// A transition's key is (0 if its target was created after the state, else 1) in
+// the upper half and the target in the lower: the smallest key is the transition
+// the record repeats first, the next one the second.
+
+__device__ __forceinline__ unsigned long long staterec_key(const Slot &sl)
+{
+    return ((unsigned long long)(sl.dst > sl.state ? 0u : 1u) << 32) | sl.dst;
+}
 
 __global__ void sam_staterec_init_kernel(const LinkPair *pairs, LinkRec *rec, uint32_t n_states)
 {
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t s = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; s < n_states; s += stride) {
         LinkRec r;
-        r.itok = kNil; r.idst = kNil; r.iendpos = 0;
+        r.itok = 0;                                            // transitions seen
+        r.idst = kNil;
+        r.iendpos = kNil; r.itok2 = kNil;                      // first key
+        r.idst2 = kNil; r.iendpos2 = kNil;                     // second key
         r.link = pairs[s].link; r.lenlink = pairs[s].lenlink;
-        r.pad[0] = r.pad[1] = r.pad[2] = 0;
         rec[s] = r;
     }
 }
 
-// pass 0: idst = the nearest target created after the state; pass 1: its token
-// and end position (a state has one transition per target at most)
+// pass 0: count, smallest key; pass 1: smallest key but the first
 __global__ void sam_staterec_pick_kernel(const Slot *slots, LinkRec *rec, uint64_t n_slots, int pass)
 {
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_slots; i += stride) {
         const Slot sl = slots[i];
-        if (sl.state == kNil || sl.dst <= sl.state) continue;
+        if (sl.state == kNil) continue;
+        LinkRec *r = &rec[sl.state];
+        unsigned long long *k0 = reinterpret_cast<unsigned long long *>(&r->iendpos);
+        unsigned long long *k1 = reinterpret_cast<unsigned long long *>(&r->idst2);
+        const unsigned long long key = staterec_key(sl);
         if (pass == 0) {
-            atomicMin(&rec[sl.state].idst, sl.dst);
-        } else if (rec[sl.state].idst == sl.dst) {
-            rec[sl.state].itok = sl.token;
-            rec[sl.state].iendpos = sl.w;
+            atomicAdd(&r->itok, 1u);
+            atomicMin(k0, key);
+        } else if (key != *k0) {
+            atomicMin(k1, key);
         }
     }
 }
 
+// wide[s / 32] bit s % 32: the state has more transitions than its record repeats;
+// the record's targets move to their places, tokens and end positions follow in the
+// next pass
+__global__ void sam_staterec_settle_kernel(LinkRec *rec, uint32_t *wide, uint32_t n_states)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t s = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; s < n_states; s += stride) {
+        LinkRec r = rec[s];
+        if (r.itok > 2) atomicOr(&wide[s >> 5], 1u << (s & 31));
+        const uint32_t d0 = r.iendpos, d1 = r.idst2;           // lower halves of the two keys
+        r.itok = kNil; r.idst = d0; r.iendpos = 0;
+        r.itok2 = kNil; r.idst2 = d1; r.iendpos2 = 0;
+        rec[s] = r;
+    }
+}
+
+__device__ __forceinline__ uint32_t wide_flag(const uint32_t *wide, uint32_t s)
+{
+    return ((wide[s >> 5] >> (s & 31)) & 1u) ? kWideBit : 0u;
+}
+
+// tokens and end positions of the repeated transitions; every slot's end position
+// gets the wide flag of its target
+__global__ void sam_staterec_fill_kernel(Slot *slots, LinkRec *rec, const uint32_t *wide,
+                                         uint64_t n_slots)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_slots; i += stride) {
+        const Slot sl = slots[i];
+        if (sl.state == kNil) continue;
+        const uint32_t w = sl.w | wide_flag(wide, sl.dst);
+        slots[i].w = w;
+        LinkRec *r = &rec[sl.state];
+        if (r->idst == sl.dst) { r->itok = sl.token; r->iendpos = w; }
+        else if (r->idst2 == sl.dst) { r->itok2 = sl.token; r->iendpos2 = w; }
+    }
+}
+
+// the wide flag of the suffix link's state, and of the root's targets
+__global__ void sam_staterec_links_kernel(LinkRec *rec, RootEnt *root, const uint32_t *wide,
+                                          uint32_t n_states, uint32_t vocab)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t s = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; s < n_states; s += stride) {
+        rec[s].lenlink |= wide_flag(wide, rec[s].link);
+        if (s < vocab && root[s].dst) root[s].endpos |= wide_flag(wide, root[s].dst);
+    }
+    // a vocabulary larger than the state count (tiny corpora)
+    for (uint64_t t = n_states + (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; t < vocab; t += stride)
+        if (root[t].dst) root[t].endpos |= wide_flag(wide, root[t].dst);
+}
+
 // ---- launchers (called from the C ABI) ------------------------------------
 
-hipError_t launch_staterec(const LinkPair *pairs, const Slot *slots, LinkRec *linkrec,
-                           uint32_t n_states, uint64_t n_slots, hipStream_t stream)
+hipError_t launch_staterec(const LinkPair *pairs, Slot *slots, RootEnt *root, LinkRec *linkrec,
+                           uint32_t *wide, uint32_t n_states, uint64_t n_slots, uint32_t vocab,
+                           hipStream_t stream)
 {
     hipLaunchKernelGGL(sam_staterec_init_kernel, dim3(4096), dim3(256), 0, stream, pairs, linkrec,
                        n_states);
@@ -1812,6 +1948,12 @@ hipError_t launch_staterec(const LinkPair *pairs, const Slot *slots, LinkRec *li
                        n_slots, 0);
     hipLaunchKernelGGL(sam_staterec_pick_kernel, dim3(8192), dim3(256), 0, stream, slots, linkrec,
                        n_slots, 1);
+    hipLaunchKernelGGL(sam_staterec_settle_kernel, dim3(4096), dim3(256), 0, stream, linkrec, wide,
+                       n_states);
+    hipLaunchKernelGGL(sam_staterec_fill_kernel, dim3(8192), dim3(256), 0, stream, slots, linkrec,
+                       wide, n_slots);
+    hipLaunchKernelGGL(sam_staterec_links_kernel, dim3(4096), dim3(256), 0, stream, linkrec, root,
+                       wide, n_states, vocab);
     return hipGetLastError();
 }
 

@@ -5,12 +5,15 @@
 //
 //  static automaton (read-only on the device)
 //    text[n]                 int32 corpus
-//    linkrec[n_states]       {one transition inline, link, length(link)} 32 B
+//    linkrec[n_states]       {two transitions inline, link, length(link)} 32 B
 //    root[vocab]             {target, min_endpos(target)}, target 0 = none  8 B
 //    slots[n_buckets * 8]    {state, token, target, min_endpos(target)} 16 B
 //                            open addressing, 128-byte buckets of 8 slots,
 //                            linear over buckets; root's transitions are not
 //                            in it (they are in root[]).
+//    Every min_endpos(target) and every length(link) on the device carries, in
+//    bit 31, whether the state it leads to is WIDE: has more than the two
+//    transitions its record repeats.  Only a wide state's lookups need a bucket.
 //    topk[n_states * k]      {token, target, probability}, optional     12 B
 //                            (Algorithm 3; only for tree drafts)
 //
@@ -42,7 +45,8 @@ struct Slot {            // 16 B
     uint32_t state;      // source state, kNil = empty slot
     uint32_t token;
     uint32_t dst;
-    uint32_t w;          // static: min_endpos(dst); dynamic and host build: next slot of `state`
+    uint32_t w;          // static: min_endpos(dst) (on the device | wide(dst) << 31);
+                         // dynamic and host build: next slot of `state`
 };
 
 struct LinkPair {        // 8 B: what the host hands over per state
@@ -51,24 +55,30 @@ struct LinkPair {        // 8 B: what the host hands over per state
 };
 
 // 32 B per state of the static automaton, built on the device from the link
-// pairs and the slot table.  Besides the suffix link it repeats ONE of the
-// state's transitions: the one to the nearest state created after it.  For a
-// state that stands for a prefix of the corpus this is the transition to the
-// next prefix, whose record is the next or next-but-one in this array -- so
-// while a sequence follows a stretch of the corpus, its lookups read
-// consecutive records (four to a cache line) instead of one random bucket each.
+// pairs and the slot table.  Besides the suffix link it repeats TWO of the
+// state's transitions: first those to states created after it, nearest first,
+// then those to older states, lowest id first.  For a state that stands for a
+// prefix of the corpus the first one is the transition to the next prefix, whose
+// record is the next or next-but-one in this array -- so while a sequence follows
+// a stretch of the corpus, its lookups read consecutive records (four to a cache
+// line) instead of one random bucket each.  A state with at most two transitions
+// (most states: the deep ones) is answered by its record alone, hit or miss.
 struct LinkRec {
-    uint32_t itok;       // token of the repeated transition, kNil = none
+    uint32_t itok;       // token of the first repeated transition, kNil = none
     uint32_t idst;       // its target
-    uint32_t iendpos;    // min_endpos(target)
+    uint32_t iendpos;    // min_endpos(target) | wide(target) << 31
+    uint32_t itok2;      // the second one, kNil = none
+    uint32_t idst2;
+    uint32_t iendpos2;
     uint32_t link;       // link(s) (0 for the root and for states of length 1)
-    uint32_t lenlink;    // len(link(s))
-    uint32_t pad[3];
+    uint32_t lenlink;    // len(link(s)) | wide(link(s)) << 31
 };
+
+constexpr uint32_t kWideBit = 0x80000000u;   // see above; lengths and end positions are < 2^31
 
 struct RootEnt {         // 8 B, static automaton; dst == 0 means no transition
     uint32_t dst;
-    uint32_t endpos;
+    uint32_t endpos;     // on the device: | wide(dst) << 31
 };
 
 struct TopEnt {          // 12 B, static automaton, k per state; dst == 0 means unused
@@ -93,7 +103,7 @@ struct DynRec {          // 32 B, dynamic automaton
 
 // per-sequence bookkeeping, 64 B
 struct SeqMeta {
-    uint32_t s1, l1, e1;     // static cursor: state, match length, min_endpos(state)
+    uint32_t s1, l1, e1;     // static cursor: state, match length, min_endpos(state) | wide << 31
     uint32_t n;              // tokens in the sequence so far
     uint32_t n_states;
     uint32_t last;

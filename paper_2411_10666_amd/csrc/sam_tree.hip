@@ -38,9 +38,11 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x)
 // Tree draft by best-first expansion over the top-k successors (Algorithm 4),
 // one wavefront per sequence.  The priority queue lives in LDS as an append-only
 // array; an entry's key packs (probability bits, ~push index), so the maximum
-// key is the largest probability and, among equals, the entry pushed first.  A
-// pop is a strided scan plus two 32-bit wave reductions; the k children of the popped
-// state are fetched by k lanes in one request and appended in table order.
+// key is the largest probability and, among equals, the entry pushed first.  The
+// k children of the popped state are fetched by k lanes in one request and appended
+// in table order; while that request travels, the lanes scan the entries already
+// queued, so that the next pop (two 32-bit wave reductions over the scan's result and
+// the new children) is known as soon as the children are.
 // Probabilities are float products rounded once per edge.
 __global__ __launch_bounds__(64) void sam_tree_kernel(StaticView S, BatchView B, int max_size,
                                                        int32_t *__restrict__ tokens,
@@ -67,40 +69,55 @@ __global__ __launch_bounds__(64) void sam_tree_kernel(StaticView S, BatchView B,
         }
         __syncthreads();
         int qn = 1;
-        while (dn < max_size) {
-            unsigned long long best = 0;
-            for (int i = lane; i < qn; i += 64) {
-                const unsigned long long key = qkey[i];
-                best = key > best ? key : best;
-            }
-            // the largest 64-bit key: the largest upper half, then the largest lower
-            // half among the lanes that hold that upper half
-            const uint32_t hi = wave_max_u32((uint32_t)(best >> 32));
-            const uint32_t lo = wave_max_u32((uint32_t)(best >> 32) == hi ? (uint32_t)best : 0u);
-            best = ((unsigned long long)hi << 32) | lo;
-            if (best == 0) break;                       // queue empty
+        unsigned long long best = qkey[0];              // the next entry to pop (0: queue empty)
+        while (dn < max_size && best != 0) {
             const uint32_t idx = 0xFFFFFFFFu - (uint32_t)best;
             const float p = __uint_as_float((uint32_t)(best >> 32));
             const uint32_t st = qstate[idx];
+            // the children's table row is the one dependent memory read of a pop: request
+            // it first, and look for the best of the entries already queued while it travels
+            TopEnt e = {0, 0, 0.0f};
+            if (lane < k) e = S.topk[(size_t)st * k + lane];
             if (lane == 0) {
                 tokens[(size_t)b * max_size + dn] = qtok[idx];
                 parents[(size_t)b * max_size + dn] = qpar[idx];
                 probs[(size_t)b * max_size + dn] = p;
-                qkey[idx] = 0;                          // popped
             }
-            TopEnt e = {0, 0, 0.0f};
-            if (lane < k) e = S.topk[(size_t)st * k + lane];
+            unsigned long long mine = 0;
+            for (int i = lane; i < qn; i += 256) {
+                // four independent reads per round (clamped, then masked), one wait
+                unsigned long long key[4];
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    const int at = i + 64 * u;
+                    key[u] = qkey[at < kQ ? at : kQ - 1];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    const int at = i + 64 * u;
+                    if (at >= qn || (uint32_t)at == idx) key[u] = 0;
+                    mine = key[u] > mine ? key[u] : mine;
+                }
+            }
             const bool valid = e.dst != 0;
             const unsigned long long mask = __ballot(valid);
             if (valid) {
                 const int pos = qn + __popcll(mask & ((1ull << lane) - 1ull));
                 const float pn = __fmul_rn(p, e.prob);
-                qkey[pos] = ((unsigned long long)__float_as_uint(pn) << 32) |
-                            (unsigned long long)(0xFFFFFFFFu - (uint32_t)pos);
+                const unsigned long long key = ((unsigned long long)__float_as_uint(pn) << 32) |
+                                               (unsigned long long)(0xFFFFFFFFu - (uint32_t)pos);
+                qkey[pos] = key;
                 qstate[pos] = e.dst;
                 qtok[pos] = (int32_t)e.token;
                 qpar[pos] = dn;
+                mine = key > mine ? key : mine;
             }
+            if (lane == 0) qkey[idx] = 0;               // popped
+            // the largest 64-bit key: the largest upper half, then the largest lower
+            // half among the lanes that hold that upper half
+            const uint32_t hi = wave_max_u32((uint32_t)(mine >> 32));
+            const uint32_t lo = wave_max_u32((uint32_t)(mine >> 32) == hi ? (uint32_t)mine : 0u);
+            best = ((unsigned long long)hi << 32) | lo;
             qn += __popcll(mask);
             dn++;
             __syncthreads();
