@@ -442,3 +442,48 @@ def test_prim_is_best_first_over_the_topk_tree(seed):
     best.sort(reverse=True)
     assert sorted((float(x) for x in pr), reverse=True) == best[:len(pr)]
     assert len(t) == min(max_size, len(best)) or len(best) > 4000
+
+
+# --------------------------------------------------------------------------
+# the exhaustive corpus scan (oracle/bruteforce.py), used where the checker's own
+# automaton is too slow to build
+
+@pytest.mark.parametrize("seed,vocab", [(0, 2), (1, 3), (2, 5), (3, 40), (4, 128256)])
+def test_corpus_scan_agrees_with_the_automaton(seed, vocab):
+    from oracle.bruteforce import CorpusScan
+    rng = np.random.default_rng(800 + seed)
+    corpus = rng.integers(0, vocab, size=2500).astype(np.int32)
+    if vocab > 100:                          # give large vocabularies something to match
+        corpus[1200:1300] = corpus[100:200]
+    scan = CorpusScan(corpus)
+    st = Sam.build(corpus)
+    x = rng.integers(0, vocab, size=300).astype(np.int32)
+    x[50:120] = corpus[130:200]
+    x[200:260] = corpus[2440:2500]           # a match that runs into the end of the corpus
+    L = 7
+    ob = Batch(st, corpus, [x[:0]], 1, L, 10 ** 6)        # l_bias so large that the draft is never static...
+    ob2 = Batch(st, corpus, [x[:0]], 1, L, -10 ** 6)      # ...and so small that it always is
+    for t in range(1, len(x) + 1):
+        ob.step(x[t - 1:t].reshape(1, 1), np.array([1], np.int32))
+        m2, src2, dl2, d2 = ob2.step(x[t - 1:t].reshape(1, 1), np.array([1], np.int32))
+        l1 = int(ob.cursors()[0][1])
+        longest, end = scan.check_static_match(x, t, l1)
+        assert longest, t
+        if l1 >= 1:
+            assert not scan.check_static_match(x, t, l1 - 1)[0] or l1 == 0      # a shorter suffix is not the longest
+            assert int(m2[0]) == l1 and int(src2[0]) == 2
+            want = scan.draft(end, L)
+            assert int(dl2[0]) == len(want) and np.array_equal(d2[0, :len(want)], want)
+        if l1 < t:
+            assert not scan.occurs(x[t - l1 - 1:t])
+
+
+def test_corpus_scan_ignores_matches_of_shifted_bytes():
+    from oracle.bruteforce import CorpusScan
+    # bytes of the corpus: 00 00 00 02 | 00 00 00 00; the token 0x00020000 (bytes 00 00 02 00)
+    # appears at byte offset 1 but is no token of the corpus
+    scan = CorpusScan(np.array([0x02000000, 0], dtype=np.int32))
+    assert scan.first_occurrence(np.array([0x00020000], dtype=np.int32)) == -1
+    assert scan.first_occurrence(np.array([0], dtype=np.int32)) == 1
+    assert scan.first_occurrence(np.array([0x02000000, 0], dtype=np.int32)) == 0
+    assert scan.draft(1, 5).tolist() == [0] and scan.draft(2, 5).tolist() == []

@@ -160,10 +160,84 @@ def test_cfg3_full_corpus():
     _sampled(CONFIGS["cfg3"], 16)
 
 
-@pytest.mark.skipif(os.environ.get("SAM_TEST_HUGE") != "1",
-                    reason="about 10 minutes and >100 GB of host memory: set SAM_TEST_HUGE=1")
 def test_cfg5_full_corpus():
-    _sampled(CONFIGS["cfg5"], 8)
+    """Config 5 at full size: 500 M-token corpus (709 M states, 59 GB of tables on the
+    device), vocabulary 128256, 1024 sequences, the whole schedule of 519 steps.  The
+    checker's own automaton of this corpus takes 8 minutes to build, so the static side
+    is checked from the definition instead (oracle/bruteforce.py: exhaustive search of
+    the corpus): on sampled (sequence, step) pairs, the reported match is the longest
+    suffix that occurs in the corpus, the draft follows the first place where it ends,
+    and a dynamic choice means that no longer suffix occurs in the corpus.  The dynamic
+    side of the sampled sequences is replayed by the checker in full (its automata are
+    small).  About 5 minutes, 70 GB of host memory."""
+    from oracle.bruteforce import CorpusScan
+    from oracle.sam_oracle import Batch
+    spec = CONFIGS["cfg5"]
+    w = make_workload(spec)
+    _say("cfg5: workload generated (corpus %d tokens)" % spec.corpus_tokens)
+    g = _gpu_schedule(w)
+    L, S = spec.draft_len, w.steps
+    seqs = sorted(set(np.linspace(0, spec.batch - 1, 12).astype(int).tolist()))
+
+    # dynamic side: the checker without a corpus gives (l2, dynamic draft) at every step
+    ob = Batch(None, None, [w.prompts[b] for b in seqs], spec.max_accept, L, spec.l_bias)
+    acc = np.ascontiguousarray(w.accepted[:, seqs])
+    cnt = np.ascontiguousarray(w.counts[:, seqs])
+    dyn_len = np.zeros((S, len(seqs)), np.int32)
+    dyn_draft = np.zeros((S, len(seqs), L), np.int32)
+    dyn_dl = np.zeros((S, len(seqs)), np.int32)
+    for s_ in range(S):
+        m, _, d_l, d = ob.step(acc[s_], cnt[s_])
+        dyn_len[s_], dyn_dl[s_], dyn_draft[s_] = m, d_l, d
+    cur = ob.cursors()
+    assert np.array_equal(g["cursors"][seqs][:, 2:], cur[:, 2:])           # (s2, l2) at the end
+    sizes = np.array([[q._L.oseq_text_len(q._h), q.dynamic().num_states, q.dynamic().num_trans]
+                      for q in ob.seqs], dtype=np.int32)
+    assert np.array_equal(g["sizes"][seqs], sizes)
+    _say("cfg5: checker replayed the dynamic side of %d sequences" % len(seqs))
+    src = g["source"][:, seqs]
+    ml = g["match_len"][:, seqs]
+    # wherever the dynamic automaton was chosen its outputs are the checker's, and
+    # wherever the static one was chosen it had the strictly longer match
+    dyn = src == 1
+    assert np.array_equal(ml[dyn], dyn_len[dyn])
+    assert np.array_equal(g["draft_len"][:, seqs][dyn], dyn_dl[dyn])
+    assert np.array_equal(g["draft"][:, seqs][dyn], dyn_draft[dyn])
+    assert (ml[src == 2] > dyn_len[src == 2]).all()
+    assert ((src == 0) == (ml == 0)).all() and (dyn_len[src == 0] == 0).all()
+
+    # static side, from the definition, on a sample
+    scan = CorpusScan(w.corpus)
+    consumed = spec.prompt_len + np.cumsum(w.counts, axis=0)              # tokens fed after step s
+    rng = np.random.default_rng(5)
+    pairs = [(int(s_), int(j)) for s_, j in zip(rng.integers(0, S, size=70),
+                                                rng.integers(0, len(seqs), size=70))]
+    n_static = n_dynamic = 0
+    for i, (s_, j) in enumerate(pairs):
+        b = seqs[j]
+        x = np.concatenate([w.prompts[b], w.generated[b]])
+        t = int(consumed[s_, b])
+        if src[s_, j] == 2:
+            longest, end = scan.check_static_match(x, t, int(ml[s_, j]))
+            assert longest and end >= 0, (s_, b)
+            want = scan.draft(end, L)
+            assert g["draft_len"][s_, b] == len(want), (s_, b)
+            assert np.array_equal(g["draft"][s_, b, :len(want)], want), (s_, b)
+            assert (g["draft"][s_, b, len(want):] == -1).all()
+            n_static += 1
+        else:
+            # dynamic (or nothing) chosen: no suffix longer than l2 occurs in the corpus
+            l2 = int(dyn_len[s_, j])
+            assert l2 + 1 > t or not scan.occurs(x[t - l2 - 1:t]), (s_, b)
+            n_dynamic += 1
+        if i % 10 == 9:
+            _say("cfg5: %d of %d sampled outputs checked against the corpus" % (i + 1, len(pairs)))
+    assert n_static >= 30, (n_static, n_dynamic)
+    # properties that hold for every sequence at any size
+    T = spec.max_seq_len
+    assert (g["sizes"][:, 0] == T).all()
+    assert (g["sizes"][:, 1] <= 2 * T - 1).all() and (g["sizes"][:, 2] <= 3 * T - 4).all()
+    assert (g["draft_len"] <= L).all() and ((g["source"] == 0) == (g["match_len"] == 0)).all()
 
 
 def test_cfg2_full_schedule_every_output():
