@@ -56,11 +56,17 @@ ALGO_BYTES_PER_MATCH_STEP = {
 }
 
 
-# HBM bytes per step launch of sam_feed_kernel from rocprofv3 counter runs
-# (FETCH_SIZE and WRITE_SIZE, each scaled by the same counter's reading for a copy
-# kernel of known size), with the digest of the kernel sources they were taken
-# on: the figure is reported only while those sources are unchanged.
+# HBM bytes of sam_feed_kernel per match-step from rocprofv3 counter runs over a whole
+# schedule (FETCH_SIZE and WRITE_SIZE, each scaled by the same counter's reading for a
+# copy kernel of known size; per launch = this figure x the launch's match-steps), with
+# the digest of the kernel sources they were taken on: the figure is reported only
+# while those sources are unchanged.
 MEASURED_TRAFFIC = {
+    # config 5, all 519 step launches of one schedule pass (8081.5 match-steps per launch):
+    # FETCH_SIZE mean 4144.50, WRITE_SIZE mean 995.16; the same counters read 131088.56
+    # and 262144.00 for a copy kernel that reads and writes 262144 KiB, i.e. 2.000 and
+    # 1.000 KiB per count: (4144.50 x 2.000 + 995.16) KiB = 9.506 MB per launch
+    "cfg5": {"bytes_per_match_step": 1176.3, "sources": "bcc63b1bc015abb8"},
 }
 
 KERNEL_SOURCES = ["sam_kernels.hip", "sam_layout.h", "sam_device.h"]
@@ -75,11 +81,12 @@ def kernel_sources_digest():
     return h.hexdigest()[:16]
 
 
-def measured_traffic(name):
+def measured_traffic(name, match_steps_per_launch):
+    """HBM bytes per launch, or None if never measured or measured on other kernels."""
     m = MEASURED_TRAFFIC.get(name)
     if not m or m["sources"] != kernel_sources_digest():
         return None
-    return m["bytes_per_launch"]
+    return m["bytes_per_match_step"] * match_steps_per_launch
 
 
 def _log(msg):
@@ -466,7 +473,7 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": measured_traffic(spec.name),
+            "traffic": measured_traffic(spec.name, per_launch),
             "algo_bytes_per_launch": algo_bytes_per_launch,
             "walk_bytes_per_launch": walk_bytes_per_launch,
             "gather_bytes_per_launch": gather_bytes_per_launch,

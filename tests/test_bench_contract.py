@@ -28,7 +28,9 @@ def test_traffic_figure_is_tied_to_the_kernel_sources():
     assert len(digest) == 16
     for name, m in bench.MEASURED_TRAFFIC.items():
         assert name in CONFIGS
-        want = m["bytes_per_launch"] if m["sources"] == digest else None
-        assert bench.measured_traffic(name) == want
-    assert bench.measured_traffic("cfg1") is None          # never measured: never reported
+        want = m["bytes_per_match_step"] * 100.0 if m["sources"] == digest else None
+        assert bench.measured_traffic(name, 100.0) == want
+    assert bench.measured_traffic("cfg1", 100.0) is None   # never measured: never reported
     assert set(bench.ALGO_BYTES_PER_MATCH_STEP) == set(CONFIGS)
+    for v in bench.ALGO_BYTES_PER_MATCH_STEP.values():
+        assert v["walk"] > v["gather"] > 0
