@@ -76,6 +76,7 @@ void HugeArray<T>::release()
 }
 
 template class HugeArray<uint32_t>;
+template class HugeArray<HostState>;
 
 namespace {
 
@@ -143,7 +144,7 @@ int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string
         return SAM_ENOMEM;
     }
     const size_t cap = (size_t)2 * n + 2;     // states <= 2n - 1 (n >= 2), 2 for n = 1
-    if (!len.reserve(cap) || !link.reserve(cap) || !endpos.reserve(cap) || !head.reserve(cap)) {
+    if (!st.reserve(cap)) {
         err = "sam_build: out of host memory for the state arrays";
         return SAM_ENOMEM;
     }
@@ -158,10 +159,7 @@ int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string
     });
 
     auto new_state = [&](uint32_t l, uint32_t lk, uint32_t ep) -> uint32_t {
-        len.push_back(l);
-        link.push_back(lk);
-        endpos.push_back(ep);
-        head.push_back(kNil);
+        st.push_back(HostState{l, lk, ep, kNil});
         return n_states++;
     };
     auto put = [&](uint64_t at, uint32_t state, uint32_t token, uint32_t dst) {
@@ -177,6 +175,11 @@ int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string
         if (progress && (i & ((1 << 24) - 1)) == 0) progress("build", i, n, user);
         const uint32_t t = (uint32_t)tokens[i];
         const uint32_t c = new_state((uint32_t)(i + 1), 0, (uint32_t)(i + 1));
+        // the next token's first insert goes into the bucket of (c, next token): ask for
+        // that line now, one token of work ahead of its use
+        if (i + 1 < n)
+            __builtin_prefetch(slots + bucket_of(hash_key(c, (uint32_t)tokens[i + 1]), n_buckets) *
+                                           kBucketSlots, 1, 0);
         uint32_t p = last;
         uint32_t q = kNil;
         uint64_t at = kNil64;          // slot of (p, t) when p is not the root
@@ -224,6 +227,13 @@ int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string
             link[c] = cl;
         }
         last = c;
+        // the next token's walk continues at link(c): its bucket and its state fields
+        if (i + 1 < n && link[c] != 0) {
+            const uint32_t up = link[c];
+            __builtin_prefetch(slots + bucket_of(hash_key(up, (uint32_t)tokens[i + 1]), n_buckets) *
+                                           kBucketSlots, 0, 0);
+            __builtin_prefetch(&st[up], 1, 0);
+        }
     }
 
     // the device reads min_endpos(target) where the build kept the list chain
@@ -234,7 +244,6 @@ int HostSam::build(const int32_t *tokens, int64_t n, int32_t vocab_, std::string
     });
     for (int32_t t = 0; t < vocab; t++)
         if (root[t].dst) root[t].endpos = endpos[root[t].dst];
-    head.release();
     return SAM_OK;
 }
 
@@ -364,11 +373,21 @@ int HostSam::save(const char *path, std::string &err) const
     h.bucket_slots = kBucketSlots;
     h.n_tokens = n_tokens; h.vocab = vocab; h.n_states = n_states; h.n_trans = n_trans;
     h.n_buckets = n_buckets;
+    // the file keeps length, link and end position as three arrays
+    auto write_field = [&](uint32_t HostState::*field) {
+        std::vector<uint32_t> chunk;
+        for (uint64_t lo = 0; lo < n_states; lo += 1u << 20) {
+            const uint64_t hi = lo + (1u << 20) < n_states ? lo + (1u << 20) : n_states;
+            chunk.resize((size_t)(hi - lo));
+            for (uint64_t s = lo; s < hi; s++) chunk[(size_t)(s - lo)] = st[s].*field;
+            if (!write_all(f, chunk.data(), chunk.size() * sizeof(uint32_t))) return false;
+        }
+        return true;
+    };
     const bool ok = write_all(f, &h, sizeof(h)) &&
                     write_all(f, text.data(), (size_t)n_tokens * sizeof(int32_t)) &&
-                    write_all(f, len.data(), (size_t)n_states * sizeof(uint32_t)) &&
-                    write_all(f, link.data(), (size_t)n_states * sizeof(uint32_t)) &&
-                    write_all(f, endpos.data(), (size_t)n_states * sizeof(uint32_t)) &&
+                    write_field(&HostState::len) && write_field(&HostState::link) &&
+                    write_field(&HostState::endpos) &&
                     write_all(f, root.data(), (size_t)vocab * sizeof(RootEnt)) &&
                     write_all(f, slots, (size_t)n_buckets * kBucketSlots * sizeof(Slot));
     const bool closed = fclose(f) == 0;
@@ -405,18 +424,27 @@ int HostSam::load(const char *path, std::string &err)
         }
         free(slots);
         slots = nullptr;
-        if (rc == SAM_OK && (!len.reserve(n_states) || !link.reserve(n_states) ||
-                             !endpos.reserve(n_states) ||
+        if (rc == SAM_OK && (!st.reserve(n_states) ||
                              !(slots = (Slot *)huge_alloc(n_slots * sizeof(Slot)))))
             rc = SAM_ENOMEM;
         if (rc != SAM_OK) {
             err = "sam_corpus_load: out of host memory";
         } else {
-            len.set_size(n_states); link.set_size(n_states); endpos.set_size(n_states);
+            st.set_size(n_states);
+            auto read_field = [&](uint32_t HostState::*field) {
+                std::vector<uint32_t> chunk;
+                for (uint64_t lo = 0; lo < n_states; lo += 1u << 20) {
+                    const uint64_t hi = lo + (1u << 20) < n_states ? lo + (1u << 20) : n_states;
+                    chunk.resize((size_t)(hi - lo));
+                    if (!read_all(f, chunk.data(), chunk.size() * sizeof(uint32_t))) return false;
+                    for (uint64_t s = lo; s < hi; s++) st[s].*field = chunk[(size_t)(s - lo)];
+                }
+                return true;
+            };
+            for (uint64_t s = 0; s < n_states; s++) st[s].head = kNil;
             const bool ok = read_all(f, text.data(), (size_t)n_tokens * sizeof(int32_t)) &&
-                            read_all(f, &len[0], (size_t)n_states * sizeof(uint32_t)) &&
-                            read_all(f, &link[0], (size_t)n_states * sizeof(uint32_t)) &&
-                            read_all(f, &endpos[0], (size_t)n_states * sizeof(uint32_t)) &&
+                            read_field(&HostState::len) && read_field(&HostState::link) &&
+                            read_field(&HostState::endpos) &&
                             read_all(f, root.data(), (size_t)vocab * sizeof(RootEnt)) &&
                             read_all(f, slots, n_slots * sizeof(Slot));
             char extra;
@@ -477,6 +505,5 @@ void HostSam::make_linkrec(std::vector<LinkPair> &out) const
     out[0] = LinkPair{0, 0};
 }
 
-void HostSam::release_build_only() { head.release(); }
 
 }  // namespace sam

@@ -32,6 +32,22 @@ private:
     size_t n_ = 0;
 };
 
+// The fields of one state, side by side: Build-SAM reads several of them whenever it
+// comes to a state (length and link on the suffix path; link, end position and list head
+// of a state it clones), and each such visit is a cache miss on the host.
+struct HostState {
+    uint32_t len, link, endpos;
+    uint32_t head;   // newest slot of the state's transition list (build only)
+};
+
+// state_field[s]: one field of HostState as if it were an array of its own
+template <uint32_t HostState::*F>
+struct StateField {
+    HugeArray<HostState> *a;
+    uint32_t &operator[](size_t i) { return (*a)[i].*F; }
+    const uint32_t &operator[](size_t i) const { return (*a)[i].*F; }
+};
+
 struct HostSam {
     int64_t  n_tokens = 0;
     int32_t  vocab = 0;
@@ -40,8 +56,11 @@ struct HostSam {
     uint64_t n_buckets = 0;
 
     std::vector<int32_t>  text;
-    HugeArray<uint32_t>   len, link, endpos;
-    HugeArray<uint32_t>   head;  // newest slot of each state's transition list (build only)
+    HugeArray<HostState>  st;
+    StateField<&HostState::len>    len{&st};
+    StateField<&HostState::link>   link{&st};
+    StateField<&HostState::endpos> endpos{&st};
+    StateField<&HostState::head>   head{&st};
     std::vector<RootEnt>  root;  // direct-indexed transitions of the root
     Slot *slots = nullptr;       // n_buckets * 8, 128-byte aligned
 
@@ -75,7 +94,6 @@ struct HostSam {
     // {link, length(link)} per state, for the device
     void make_linkrec(std::vector<LinkPair> &out) const;
 
-    void release_build_only();   // drop arrays the device does not need
 };
 
 }  // namespace sam
