@@ -55,7 +55,11 @@ def count(spec, corpus_limit=None, batch_limit=None):
     if corpus is not None and corpus_limit and len(corpus) > corpus_limit:
         corpus = corpus[:corpus_limit]
     nb = spec.batch if not batch_limit else min(spec.batch, batch_limit)
-    static = Sam.build(corpus) if corpus is not None else None
+    def progress(done, total):          # a corpus of 500 M tokens takes minutes
+        print("[count_ops] corpus automaton: %d of %d tokens" % (done, total), file=sys.stderr,
+              flush=True)
+
+    static = Sam.build(corpus, progress=progress) if corpus is not None else None
     ob = Batch(static, corpus, [w.prompts[b] for b in range(nb)], spec.max_accept,
                spec.draft_len, spec.l_bias)
     before = _totals(ob)
