@@ -55,6 +55,11 @@ __global__ __launch_bounds__(64) void sam_tree_kernel(StaticView S, BatchView B,
     __shared__ uint32_t qstate[kQ];
     __shared__ int32_t qtok[kQ];
     __shared__ int32_t qpar[kQ];
+    // the draft is collected here and written out once at the end: a store per pop would
+    // sit in the same in-order queue as the pop's table read and be waited for with it
+    __shared__ int32_t otok[kMaxTreeSize];
+    __shared__ int32_t opar[kMaxTreeSize];
+    __shared__ float   oprob[kMaxTreeSize];
     const int b = blockIdx.x;
     const int lane = threadIdx.x;
     const SeqMeta m = B.meta[b];
@@ -79,9 +84,9 @@ __global__ __launch_bounds__(64) void sam_tree_kernel(StaticView S, BatchView B,
             TopEnt e = {0, 0, 0.0f};
             if (lane < k) e = S.topk[(size_t)st * k + lane];
             if (lane == 0) {
-                tokens[(size_t)b * max_size + dn] = qtok[idx];
-                parents[(size_t)b * max_size + dn] = qpar[idx];
-                probs[(size_t)b * max_size + dn] = p;
+                otok[dn] = qtok[idx];
+                opar[dn] = qpar[idx];
+                oprob[dn] = p;
             }
             unsigned long long mine = 0;
             for (int i = lane; i < qn; i += 256) {
@@ -123,10 +128,11 @@ __global__ __launch_bounds__(64) void sam_tree_kernel(StaticView S, BatchView B,
             __syncthreads();
         }
     }
-    for (int i = dn + lane; i < max_size; i += 64) {
-        tokens[(size_t)b * max_size + i] = -1;
-        parents[(size_t)b * max_size + i] = -1;
-        probs[(size_t)b * max_size + i] = 0.0f;
+    for (int i = lane; i < max_size; i += 64) {
+        const bool have = i < dn;
+        tokens[(size_t)b * max_size + i] = have ? otok[i] : -1;
+        parents[(size_t)b * max_size + i] = have ? opar[i] : -1;
+        probs[(size_t)b * max_size + i] = have ? oprob[i] : 0.0f;
     }
     if (lane == 0) sizes[b] = dn;
 }
