@@ -397,6 +397,9 @@ def main():
                     help="skip the memory-system measurements (memory_system, latency_bound)")
     ap.add_argument("--tree-draft", default="",
                     help="K,MAX_SIZE: also time sam_batch_tree_draft (reported as tree_draft)")
+    ap.add_argument("--library-mode", type=int, default=0,
+                    help="sam_set_layout_override mode for the batches of this run (a testing "
+                         "and measuring aid, e.g. 32: step kernel without its scout waves)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB before the timed "
                          "steps (a kernel of known traffic to scale profiler counters by)")
@@ -428,6 +431,10 @@ def main():
              % (args.copy_probe_mib, args.copy_probe_mib))
         del src_t, dst_t
     tree = tuple(int(v) for v in args.tree_draft.split(",")) if args.tree_draft else None
+    if args.library_mode:
+        from paper_2411_10666_amd import binding as sam
+        sam.sam_set_layout_override(args.library_mode)
+        _log("library mode %d" % args.library_mode)
     cc = None if args.no_cpu_baseline else CpuCorpus(w)
     g = gpu_leg(w, args.steps, args.warmup, tree, before_timing=cc.wait if cc else None)
 
@@ -465,6 +472,7 @@ def main():
             "draft_len": spec.draft_len,
             "l_bias": spec.l_bias,
             "seed": spec.seed,
+            **({"library_mode": args.library_mode} if args.library_mode else {}),
         },
         "draft_tokens_per_s": g["draft_tokens"] / (g["event_ms"] * 1e-3),
         "sequence_steps_per_s": spec.batch * args.steps / (g["event_ms"] * 1e-3),

@@ -23,7 +23,7 @@ namespace {
 thread_local std::string g_err;
 int g_layout_override = 0;   // bit 0: always the wide layout, bit 1: tight slot tables,
                              // bit 2: C++ token loops, bit 3: corpus table beyond 4 GiB,
-                             // bit 4: scout waves whatever the batch size
+                             // bit 4: scout waves whatever the batch size, bit 5: never
 // Scout waves pay once the tables a step touches no longer stay in the caches from
 // one launch to the next, which is a matter of how many sequences share them.
 constexpr int kScoutMinBatch = 128;
@@ -455,7 +455,8 @@ static BatchBytes batch_configure(BatchView &v, bool has_static, int32_t batch, 
     v.l_bias = l_bias;
     v.l_threshold = -1;
     v.no_asm = (g_layout_override & 4) ? 1 : 0;
-    v.scout = ((g_layout_override & 16) || batch >= kScoutMinBatch) ? 1 : 0;
+    v.scout = ((g_layout_override & 32) == 0 &&
+               ((g_layout_override & 16) || batch >= kScoutMinBatch)) ? 1 : 0;
     v.has_static = has_static ? 1 : 0;
     BatchBytes b;
     b.text = (size_t)batch * max_seq_len * sizeof(int32_t);
@@ -750,7 +751,7 @@ int sam_set_progress_callback(sam_progress_fn fn, void *user)
 
 int sam_set_layout_override(int mode)
 {
-    if (mode < 0 || mode > 31) return fail(SAM_EINVAL, "sam_set_layout_override: mode is 0 .. 31");
+    if (mode < 0 || mode > 63) return fail(SAM_EINVAL, "sam_set_layout_override: mode is 0 .. 63");
     g_layout_override = mode;
     return SAM_OK;
 }
