@@ -2,12 +2,15 @@
 // draft gather (arxiv 2411.10666: Algorithm 1 Transfer, Algorithm 2 Expand,
 // Section 3.2 draft read and source selection, Section 3.3 update order).
 //
-// Execution shape: one workgroup of two 64-lane wavefronts per sequence.
+// Execution shape: one workgroup per sequence.
 //   wave 0  walks the static automaton (read-only tables in HBM),
 //   wave 1  extends the sequence's own dynamic automaton,
-// both over the same accepted tokens and concurrently; they meet at one
-// barrier, after which wave 0 selects the source and gathers the draft with
-// coalesced reads.  Inside a wave all control flow is wave-uniform: the lanes
+// both over the same accepted tokens and concurrently; the one that comes second
+// selects the source and gathers the draft with coalesced reads.  For large
+// batches the step kernel has two more waves per sequence, the scouts, which run
+// ahead over the step's tokens and pull the records and buckets the two walks
+// will fall back to into the caches (see "scout waves" below).
+// Inside a walking wave all control flow is wave-uniform: the lanes
 // are used to fetch a whole 128-byte hash bucket in one request and to resolve
 // it with two ballots, so a lookup costs one memory round trip whatever the
 // state's out-degree.  The path is bound by dependent memory round trips, so
@@ -1542,7 +1545,7 @@ __device__ __forceinline__ void scout_dynamic_compact(const DynSeq &D, uint32_t 
 
 }  // namespace
 
-// One workgroup (2 waves) per sequence.  kIngest: sequence b is fed
+// One workgroup per sequence: two walking waves, and with kScout two scouts.  kIngest: sequence b is fed
 // tokens[offsets[b] : offsets[b+1]) and nothing is written to the draft
 // outputs.  Otherwise: sequence b is fed the first counts[b] tokens of
 // tokens[b * max_accept ...], then source selection and draft gather.
