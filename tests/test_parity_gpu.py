@@ -149,6 +149,50 @@ def test_static_table_beyond_4_gib():
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("mode", [0, 16])
+def test_steps_replayed_from_a_hip_graph(mode):
+    """sam_batch_step allocates nothing, reads nothing back and enqueues one kernel, so a
+    step can be captured in a HIP graph: the graph is captured once over fixed input and
+    output buffers and replayed for every step of the schedule, the step's tokens copied
+    into the input buffers in between; every replay is compared with the checker.
+    mode 16: the step kernel with its scout waves."""
+    import torch
+    from paper_2411_10666_amd import binding as sam
+    spec = CONFIGS["cfg1"].scaled(corpus_tokens=30_000, batch=9, prompt_len=120, gen_len=260)
+    w = make_workload(spec)
+    prompts = [w.prompts[b] for b in range(spec.batch)]
+    r, _ = run_oracle(w.corpus, prompts, w.accepted, w.counts, spec.max_accept, spec.draft_len)
+    dev = torch.device("cuda:0")
+    B, A, L = spec.batch, spec.max_accept, spec.draft_len
+    corpus = sam.sam_build(w.corpus, spec.vocab)
+    sam.sam_set_layout_override(mode)
+    try:
+        batch = sam.sam_batch_init(corpus, torch.from_numpy(w.prompts.reshape(-1)).to(dev),
+                                   torch.from_numpy(w.prompt_offsets).to(dev), B, spec.vocab,
+                                   spec.max_seq_len, A, L, spec.l_bias)
+    finally:
+        sam.sam_set_layout_override(0)
+    i32 = dict(dtype=torch.int32, device=dev)
+    acc = torch.zeros(B, A, **i32); cnt = torch.zeros(B, **i32)
+    ml = torch.zeros(B, **i32); dl = torch.zeros(B, **i32); src = torch.zeros(B, **i32)
+    dr = torch.zeros(B, L, **i32)
+    d_acc = torch.from_numpy(w.accepted).to(dev)
+    d_cnt = torch.from_numpy(w.counts).to(dev)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    # capture records the launch without running it: the batch is not advanced here
+    with torch.cuda.graph(graph):
+        sam.sam_batch_step(batch, acc, cnt, ml, dr, dl, src)
+    _say("graph captured; replaying %d steps" % w.steps)
+    for s_ in range(w.steps):
+        acc.copy_(d_acc[s_]); cnt.copy_(d_cnt[s_])
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, key in ((ml, "match_len"), (dl, "draft_len"), (src, "source"), (dr, "draft")):
+            assert np.array_equal(got.cpu().numpy(), r[s_][key]), "step %d: %s" % (s_, key)
+    assert sam.sam_batch_status(batch) == 0
+
+
 def test_multi_document_corpus_with_separators():
     """Section 3.1: the documents of a corpus are joined by a separator token into one
     string and one automaton.  40 documents joined by token vocab-1; sequences copy
