@@ -336,7 +336,8 @@ int sam_batch_status(const sam_batch *batch, uint32_t *status, void *hip_stream)
  * corpus (about that much host and device memory), so that table offsets beyond
  * 32 bits are reached with a corpus that builds in a moment; bit 4 makes the
  * step kernel of every later sam_batch_init run with its two prefetching waves,
- * which otherwise join only for batches of 128 sequences or more; bit 5 keeps them
+ * which otherwise join for batches of 128 sequences or more and for corpus
+ * automata larger than 256 MB; bit 5 keeps them
  * out whatever the batch size (for measuring what they cost and bring).  mode 0
  * restores the defaults.  Results are identical in every mode.
  */

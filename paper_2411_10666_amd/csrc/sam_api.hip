@@ -24,9 +24,13 @@ thread_local std::string g_err;
 int g_layout_override = 0;   // bit 0: always the wide layout, bit 1: tight slot tables,
                              // bit 2: C++ token loops, bit 3: corpus table beyond 4 GiB,
                              // bit 4: scout waves whatever the batch size, bit 5: never
-// Scout waves pay once the tables a step touches no longer stay in the caches from
-// one launch to the next, which is a matter of how many sequences share them.
-constexpr int kScoutMinBatch = 128;
+// Scout waves pay once the tables a step touches no longer stay in the caches from one
+// launch to the next: the per-sequence tables when many sequences share the caches, the
+// corpus automaton when it is larger than the last-level cache (256 MB).  Measured:
+// 8 sequences over 12 MB of corpus tables +4.5 % per step with scouts, 64 over 1.2 GB
+// -2 %, 256 over 12 GB -15 %.
+constexpr int     kScoutMinBatch = 128;
+constexpr int64_t kScoutMinCorpusBytes = 256ll << 20;
 // buckets of 128 bytes that make a transition table of 4.5 GiB
 constexpr uint64_t kHugeTableBuckets = (1ull << 25) + (1ull << 22);
 HostSam::ProgressFn g_progress = nullptr;
@@ -433,10 +437,11 @@ static int batch_check_offsets(const char *fn, const int64_t *offs, int32_t batc
 // Sizes of the per-sequence tables for these parameters.
 struct BatchBytes { size_t text, rec, slots, meta; };
 
-static BatchBytes batch_configure(BatchView &v, bool has_static, int32_t batch, int32_t vocab,
-                                  int32_t max_seq_len, int32_t max_accept, int32_t draft_len,
-                                  int32_t l_bias)
+static BatchBytes batch_configure(BatchView &v, const sam_corpus *corpus, int32_t batch,
+                                  int32_t vocab, int32_t max_seq_len, int32_t max_accept,
+                                  int32_t draft_len, int32_t l_bias)
 {
+    const bool has_static = corpus != nullptr;
     v.batch = batch;
     v.vocab = vocab;
     v.max_seq_len = (uint32_t)max_seq_len;
@@ -456,7 +461,8 @@ static BatchBytes batch_configure(BatchView &v, bool has_static, int32_t batch, 
     v.l_threshold = -1;
     v.no_asm = (g_layout_override & 4) ? 1 : 0;
     v.scout = ((g_layout_override & 32) == 0 &&
-               ((g_layout_override & 16) || batch >= kScoutMinBatch)) ? 1 : 0;
+               ((g_layout_override & 16) || batch >= kScoutMinBatch ||
+                (corpus && corpus->device_bytes > kScoutMinCorpusBytes))) ? 1 : 0;
     v.has_static = has_static ? 1 : 0;
     BatchBytes b;
     b.text = (size_t)batch * max_seq_len * sizeof(int32_t);
@@ -495,8 +501,8 @@ int sam_batch_init(const sam_corpus *corpus, const int32_t *prompt_tokens,
     if (!bt) return fail(SAM_ENOMEM, "sam_batch_init: out of host memory");
     bt->corpus = corpus;
     BatchView &v = bt->view;
-    const BatchBytes bb = batch_configure(v, corpus != nullptr, batch, vocab, max_seq_len,
-                                          max_accept, draft_len, l_bias);
+    const BatchBytes bb = batch_configure(v, corpus, batch, vocab, max_seq_len, max_accept,
+                                          draft_len, l_bias);
     hipError_t e;
     if ((e = hipMalloc((void **)&v.dyn_text, bb.text)) != hipSuccess ||
         (e = hipMalloc((void **)&v.dyn_rec, bb.rec)) != hipSuccess ||
@@ -552,8 +558,8 @@ int sam_batch_init_noalloc(const sam_corpus *corpus, const int32_t *prompt_token
                                     std::to_string(kMaxDevices - 1));
 
     BatchView v = {};
-    const BatchBytes bb = batch_configure(v, corpus != nullptr, batch, vocab, max_seq_len,
-                                          max_accept, draft_len, l_bias);
+    const BatchBytes bb = batch_configure(v, corpus, batch, vocab, max_seq_len, max_accept,
+                                          draft_len, l_bias);
     auto up = [](size_t x) { return (x + 255) / 256 * 256; };
     const size_t o_text = 0, o_rec = o_text + up(bb.text), o_slots = o_rec + up(bb.rec),
                  o_meta = o_slots + up(bb.slots), o_status = o_meta + up(bb.meta),
