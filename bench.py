@@ -50,8 +50,8 @@ ALGO_BYTES_PER_MATCH_STEP = {
     "cfg2": {"walk": 211.1, "gather": 34.0, "corpus": 10_000_000},
     "cfg3": {"walk": 206.8, "gather": 34.2, "corpus": 100_000_000},
     "cfg4": {"walk": 249.6, "gather": 33.8, "corpus": 0},
-    # (counted once on the host of an MI355X machine: the checker's automaton of the whole
-    # 500 M-token corpus takes 8 minutes to build)
+    # (counted once, apart from the benchmark runs: the checker's automaton of the whole
+    # 500 M-token corpus takes 8 minutes and 100 GB of host memory to build)
     "cfg5": {"walk": 207.0, "gather": 34.5, "corpus": 500_000_000},
 }
 
