@@ -146,6 +146,7 @@ static int corpus_upload(sam_corpus *c)
     const size_t b_lr = (size_t)h.n_states * sizeof(LinkRec);
     const size_t b_root = (size_t)h.vocab * sizeof(RootEnt);
     const size_t b_slots = (size_t)h.n_buckets * kBucketSlots * sizeof(Slot);
+    size_t b_slots_dev = b_slots;      // what stays on the device in the end
     HIP_TRY(hipGetDevice(&c->device));
     HIP_TRY(hipMalloc(&c->d_text, b_text));
     HIP_TRY(hipMalloc(&c->d_linkrec, b_lr));
@@ -169,17 +170,51 @@ static int corpus_upload(sam_corpus *c)
                                 h.n_buckets * kBucketSlots, (uint32_t)h.vocab, nullptr);
         if (e == hipSuccess) e = hipDeviceSynchronize();
         (void)hipFree(d_pairs);
+        // The walks only ever look up transitions of wide states (a narrow state's record
+        // holds all of its own): the table they probe is rebuilt with those alone, at load
+        // 0.5, and the full one freed.  (Not in the testing mode that wants a table beyond
+        // 4 GiB.)
+        uint64_t n_buckets = h.n_buckets;
+        if (e == hipSuccess && (g_layout_override & 8) == 0) {
+            unsigned long long *d_count = nullptr, n_wide = 0;
+            void *d_new = nullptr;
+            e = hipMalloc((void **)&d_count, sizeof(*d_count));
+            if (e == hipSuccess) e = hipMemset(d_count, 0, sizeof(*d_count));
+            if (e == hipSuccess)
+                e = launch_count_wide((const Slot *)c->d_slots, (const uint32_t *)d_wide,
+                                      h.n_buckets * kBucketSlots, d_count, nullptr);
+            if (e == hipSuccess) e = hipMemcpy(&n_wide, d_count, sizeof(n_wide), hipMemcpyDeviceToHost);
+            if (d_count) (void)hipFree(d_count);
+            const uint64_t nb_new = (2 * (uint64_t)n_wide + 64 + kBucketSlots - 1) / kBucketSlots;
+            if (e == hipSuccess && nb_new < h.n_buckets) {
+                const size_t b_new = (size_t)nb_new * kBucketSlots * sizeof(Slot);
+                e = hipMalloc(&d_new, b_new);
+                if (e == hipSuccess) e = launch_fill_empty(d_new, b_new, nullptr);
+                if (e == hipSuccess)
+                    e = launch_compact_slots((const Slot *)c->d_slots, (const uint32_t *)d_wide,
+                                             h.n_buckets * kBucketSlots, (Slot *)d_new, nb_new, nullptr);
+                if (e == hipSuccess) e = hipDeviceSynchronize();
+                if (e == hipSuccess) {
+                    (void)hipFree(c->d_slots);
+                    c->d_slots = d_new;
+                    n_buckets = nb_new;
+                } else if (d_new) {
+                    (void)hipFree(d_new);
+                }
+            }
+        }
         if (d_wide) (void)hipFree(d_wide);
         if (e != hipSuccess) return fail_hip("sam_build: state records", e);
+        b_slots_dev = (size_t)n_buckets * kBucketSlots * sizeof(Slot);
+        c->view.n_buckets = n_buckets;
     }
     c->view.text = (const int32_t *)c->d_text;
     c->view.linkrec = (const LinkRec *)c->d_linkrec;
     c->view.root = (const RootEnt *)c->d_root;
     c->view.slots = (const Slot *)c->d_slots;
-    c->view.n_buckets = h.n_buckets;
     c->view.n_tokens = (uint32_t)h.n_tokens;
     c->view.n_states = h.n_states;
-    c->device_bytes = (int64_t)(b_text + b_lr + b_root + b_slots);
+    c->device_bytes = (int64_t)(b_text + b_lr + b_root + b_slots_dev);
     c->on_device = true;
     if (c->device >= 0 && c->device < kMaxDevices) {
         // a set-up call: do the one-time lookup of the fixed buffer here, so that a later

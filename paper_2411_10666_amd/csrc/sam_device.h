@@ -60,6 +60,12 @@ hipError_t launch_feed(const StaticView &S, const BatchView &B, const int32_t *s
 hipError_t launch_staterec(const LinkPair *pairs, Slot *slots, RootEnt *root, LinkRec *linkrec,
                            uint32_t *wide, uint32_t n_states, uint64_t n_slots, uint32_t vocab,
                            hipStream_t stream);
+// Transitions of wide states among the n_slots slots (added to *count, device memory), and
+// their insertion into a table of n_buckets buckets whose keys are all kNil.
+hipError_t launch_count_wide(const Slot *slots, const uint32_t *wide, uint64_t n_slots,
+                             unsigned long long *count, hipStream_t stream);
+hipError_t launch_compact_slots(const Slot *slots, const uint32_t *wide, uint64_t n_slots,
+                                Slot *out, uint64_t n_buckets, hipStream_t stream);
 hipError_t launch_replay(const StaticView &S, const BatchView &B, int n_steps,
                          const int32_t *accepted, const int32_t *counts, int32_t *match_len,
                          int32_t *draft, int32_t *draft_len, int32_t *source, hipStream_t stream);

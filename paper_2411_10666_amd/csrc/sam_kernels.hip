@@ -1939,6 +1939,52 @@ __global__ void sam_staterec_links_kernel(LinkRec *rec, RootEnt *root, const uin
         if (root[t].dst) root[t].endpos |= wide_flag(wide, root[t].dst);
 }
 
+// ---- the device's transition table: wide states only --------------------------
+//
+// A narrow state (at most two transitions) is answered by its record, so no lookup
+// ever asks the table for one of its transitions.  The table the walks probe is
+// therefore rebuilt on the device with the transitions of wide states alone, at
+// load 0.5: a fraction of the host's table, which holds every transition.
+
+__global__ void sam_count_wide_kernel(const Slot *slots, const uint32_t *wide, uint64_t n_slots,
+                                      unsigned long long *count)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    unsigned long long mine = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_slots; i += stride) {
+        const uint32_t st = slots[i].state;
+        if (st != kNil && wide_flag(wide, st)) mine++;
+    }
+    if (mine) atomicAdd(count, mine);
+}
+
+// Insert every transition of a wide state into the new table (all keys kNil before):
+// a slot is claimed by an atomic exchange of its state word, the other words follow;
+// nothing looks the table up before this kernel has finished.
+__global__ void sam_compact_slots_kernel(const Slot *slots, const uint32_t *wide, uint64_t n_slots,
+                                         Slot *out, uint64_t n_buckets)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_slots; i += stride) {
+        const Slot sl = slots[i];
+        if (sl.state == kNil || !wide_flag(wide, sl.state)) continue;
+        uint64_t b = bucket_of(hash_key(sl.state, sl.token), n_buckets);
+        bool placed = false;
+        for (uint64_t left = n_buckets; left && !placed; left--) {
+            for (int j = 0; j < kBucketSlots && !placed; j++) {
+                Slot *dst = out + b * kBucketSlots + j;
+                if (dst->state == kNil && atomicCAS(&dst->state, kNil, sl.state) == kNil) {
+                    dst->token = sl.token;
+                    dst->dst = sl.dst;
+                    dst->w = sl.w;
+                    placed = true;
+                }
+            }
+            b = (b + 1 == n_buckets) ? 0 : b + 1;
+        }
+    }
+}
+
 // ---- launchers (called from the C ABI) ------------------------------------
 
 hipError_t launch_staterec(const LinkPair *pairs, Slot *slots, RootEnt *root, LinkRec *linkrec,
@@ -1957,6 +2003,22 @@ hipError_t launch_staterec(const LinkPair *pairs, Slot *slots, RootEnt *root, Li
                        wide, n_slots);
     hipLaunchKernelGGL(sam_staterec_links_kernel, dim3(4096), dim3(256), 0, stream, linkrec, root,
                        wide, n_states, vocab);
+    return hipGetLastError();
+}
+
+hipError_t launch_count_wide(const Slot *slots, const uint32_t *wide, uint64_t n_slots,
+                             unsigned long long *count, hipStream_t stream)
+{
+    hipLaunchKernelGGL(sam_count_wide_kernel, dim3(8192), dim3(256), 0, stream, slots, wide,
+                       n_slots, count);
+    return hipGetLastError();
+}
+
+hipError_t launch_compact_slots(const Slot *slots, const uint32_t *wide, uint64_t n_slots,
+                                Slot *out, uint64_t n_buckets, hipStream_t stream)
+{
+    hipLaunchKernelGGL(sam_compact_slots_kernel, dim3(8192), dim3(256), 0, stream, slots, wide,
+                       n_slots, out, n_buckets);
     return hipGetLastError();
 }
 
