@@ -63,19 +63,20 @@ ALGO_BYTES_PER_MATCH_STEP = {
 # while those sources are unchanged.
 MEASURED_TRAFFIC = {
     # config 5, all 519 step launches of one schedule pass (8081.5 match-steps per launch):
-    # FETCH_SIZE mean 4144.50, WRITE_SIZE mean 995.16; the same counters read 131088.56
+    # FETCH_SIZE mean 4145.76, WRITE_SIZE mean 995.16; the same counters read 131089.00
     # and 262144.00 for a copy kernel that reads and writes 262144 KiB, i.e. 2.000 and
-    # 1.000 KiB per count: (4144.50 x 2.000 + 995.16) KiB = 9.506 MB per launch
-    "cfg5": {"bytes_per_match_step": 1176.3, "sources": "cc8ff06b9e437bf6"},
-    # config 3, 673 launches (1558.1 match-steps each): FETCH_SIZE 936.34 x 2.000 +
-    # WRITE_SIZE 204.75 x 1.000 KiB = 2.127 MB per launch
-    "cfg3": {"bytes_per_match_step": 1365.1, "sources": "cc8ff06b9e437bf6"},
-    # config 4 (no corpus), 273 launches (7681.9 match-steps each): 2534.50 x 2.000 +
-    # 1011.09 x 1.000 KiB = 6.225 MB per launch
-    "cfg4": {"bytes_per_match_step": 810.4, "sources": "cc8ff06b9e437bf6"},
+    # 1.000 KiB per count: (4145.76 x 2.000 + 995.16) KiB = 9.510 MB per launch
+    "cfg5": {"bytes_per_match_step": 1176.7, "sources": "db8117b4f7ddbdcd"},
+    # config 3, 673 launches (1558.1 match-steps each): FETCH_SIZE 938.57 x 2.000 +
+    # WRITE_SIZE 204.75 x 1.000 KiB = 2.132 MB per launch
+    "cfg3": {"bytes_per_match_step": 1368.3, "sources": "db8117b4f7ddbdcd"},
+    # config 4 (no corpus), 273 launches (7681.9 match-steps each): 2537.59 x 2.000 +
+    # 1011.09 x 1.000 KiB = 6.232 MB per launch
+    "cfg4": {"bytes_per_match_step": 811.3, "sources": "db8117b4f7ddbdcd"},
 }
 
-KERNEL_SOURCES = ["sam_kernels.hip", "sam_layout.h", "sam_device.h"]
+# the kernels, the layouts, and the file that sets the device tables up
+KERNEL_SOURCES = ["sam_kernels.hip", "sam_layout.h", "sam_device.h", "sam_api.hip"]
 
 
 def kernel_sources_digest():
