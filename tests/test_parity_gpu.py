@@ -149,6 +149,54 @@ def test_static_table_beyond_4_gib():
     torch.cuda.empty_cache()
 
 
+def _degree_corpus(kind, n, rng):
+    if kind == "all_distinct":        # every state but the root has at most one transition
+        return rng.permutation(n).astype(np.int32), n
+    if kind == "periodic":            # abcabc...: one successor everywhere
+        return (np.arange(n) % 7).astype(np.int32), 7
+    if kind == "two_way":             # binary: no state can have more than two
+        return rng.integers(0, 2, size=n).astype(np.int32), 2
+    if kind == "three_way":           # the smallest alphabet with wide states
+        return rng.integers(0, 3, size=n).astype(np.int32), 3
+    assert kind == "dense"            # short contexts followed by most of the alphabet
+    return rng.integers(0, 12, size=n).astype(np.int32), 12
+
+
+@pytest.mark.parametrize("kind", ["all_distinct", "periodic", "two_way", "three_way", "dense"])
+def test_corpora_by_out_degree(kind):
+    """The device keeps a state's first two transitions in its record and only those of
+    states with more in its table: corpora whose states have none, some or mostly more."""
+    from paper_2411_10666_amd import binding as sam
+    rng = np.random.default_rng(len(kind))
+    n = 6000
+    corpus, vocab = _degree_corpus(kind, n, rng)
+    B, T, A, L, steps = 11, 400, 7, 10, 40
+    _say("corpus by out-degree: %s vocab=%d" % (kind, vocab))
+    prompts = []
+    for b in range(B):
+        j = int(rng.integers(0, n - 40))
+        p = corpus[j:j + 30].copy()
+        p[rng.integers(0, 30, size=3)] = rng.integers(0, vocab, size=3)
+        prompts.append(p.astype(np.int32))
+    acc = rng.integers(0, vocab, size=(steps, B, A)).astype(np.int32)
+    counts = rng.integers(0, A + 1, size=(steps, B)).astype(np.int32)
+    for s_ in range(steps):
+        for b in range(B):
+            c = int(counts[s_, b])
+            if c >= 2 and rng.random() < 0.7:
+                j = int(rng.integers(0, n - c))
+                acc[s_, b, :c] = corpus[j:j + c]
+    gc = sam.sam_build(corpus, vocab)
+    n_states, n_trans, dev_bytes = sam.sam_corpus_info(gc)
+    g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L, gpu_corpus=gc)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r)
+    if kind in ("periodic", "two_way"):
+        # nothing but (at most) the root is wide: text, 32-byte records, and next to no table
+        assert dev_bytes < 4 * n + 32 * n_states + 16 * vocab + 4096
+
+
 @pytest.mark.parametrize("mode", [0, 16])
 def test_steps_replayed_from_a_hip_graph(mode):
     """sam_batch_step allocates nothing, reads nothing back and enqueues one kernel, so a
