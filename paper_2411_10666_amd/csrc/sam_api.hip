@@ -28,8 +28,12 @@ int g_layout_override = 0;   // bit 0: always the wide layout, bit 1: tight slot
 // launch to the next: the per-sequence tables when many sequences share the caches, the
 // corpus automaton when it is larger than the last-level cache (256 MB).  Measured:
 // 8 sequences over 12 MB of corpus tables +4.5 % per step with scouts, 64 over 1.2 GB
-// -2 %, 256 over 12 GB -15 %.
+// -2 %, 256 over 12 GB -15 %.  They stop paying once the walking waves alone fill the
+// chip: with more than six sequences per compute unit the scouts take wave slots and
+// issue cycles from other sequences' walks (1024 sequences on 256 units over 6 GB of
+// tables -9 % per step with scouts, 1536 -6 %, 2048 +9 %, 4096 +19 %, 8192 +27 %).
 constexpr int     kScoutMinBatch = 128;
+constexpr int     kScoutMaxSeqPerCu = 6;
 constexpr int64_t kScoutMinCorpusBytes = 256ll << 20;
 // buckets of 128 bytes that make a transition table of 4.5 GiB
 constexpr uint64_t kHugeTableBuckets = (1ull << 25) + (1ull << 22);
@@ -495,9 +499,15 @@ static BatchBytes batch_configure(BatchView &v, const sam_corpus *corpus, int32_
     v.l_bias = l_bias;
     v.l_threshold = -1;
     v.no_asm = (g_layout_override & 4) ? 1 : 0;
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        n_cu = 0;                          // unknown: no upper limit
+    const bool scouts_fit = n_cu <= 0 || (int64_t)batch <= (int64_t)n_cu * kScoutMaxSeqPerCu;
     v.scout = ((g_layout_override & 32) == 0 &&
-               ((g_layout_override & 16) || batch >= kScoutMinBatch ||
-                (corpus && corpus->device_bytes > kScoutMinCorpusBytes))) ? 1 : 0;
+               ((g_layout_override & 16) ||
+                (scouts_fit && (batch >= kScoutMinBatch ||
+                                (corpus && corpus->device_bytes > kScoutMinCorpusBytes))))) ? 1 : 0;
     v.has_static = has_static ? 1 : 0;
     BatchBytes b;
     b.text = (size_t)batch * max_seq_len * sizeof(int32_t);
