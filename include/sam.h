@@ -74,10 +74,13 @@ const char *sam_build_id(void);
 
 /*
  * Build-SAM (Algorithm 2) over `corpus_tokens` on the host, then copy the
- * automaton to device memory as flat arrays: the corpus text, one
- * {link, length(link)} record per state, a direct-indexed table of the root's
- * transitions and a bucketed open-addressed (state, token) -> {target,
- * min_endpos(target)} hash for all other transitions.
+ * automaton to device memory as flat arrays: the corpus text, one record per
+ * state with its suffix link, the link's length and up to two of its
+ * transitions, a direct-indexed table of the root's transitions and a bucketed
+ * open-addressed (state, token) -> {target, min_endpos(target)} hash that holds
+ * the transitions of the states with more than two.  The device holds the
+ * complete transition table while the records are made (sam_corpus_info
+ * reports what stays afterwards).
  *   corpus_tokens : host, int32 [n_tokens]; a multi-document corpus is passed
  *                   already joined by a separator token (Section 3.1).
  *   n_tokens      : 1 .. 2^31-2.   vocab : 1 .. 2^31-1.
