@@ -41,8 +41,8 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x)
 // key is the largest probability and, among equals, the entry pushed first.  The
 // k children of the popped state are fetched by k lanes in one request and appended
 // in table order; while that request travels, the lanes scan the entries already
-// queued, so that the next pop (two 32-bit wave reductions over the scan's result and
-// the new children) is known as soon as the children are.
+// queued and reduce them to their best (two 32-bit wave reductions), so that the next
+// pop (that best, or the first of the new children) is known as soon as the children are.
 // Probabilities are float products rounded once per edge.
 __global__ __launch_bounds__(64) void sam_tree_kernel(StaticView S, BatchView B, int max_size,
                                                        int32_t *__restrict__ tokens,
@@ -104,8 +104,18 @@ __global__ __launch_bounds__(64) void sam_tree_kernel(StaticView S, BatchView B,
                     mine = key[u] > mine ? key[u] : mine;
                 }
             }
+            // the best of the entries already queued, still in the shadow of the request: the
+            // largest 64-bit key is the largest upper half, then the largest lower half
+            // among the lanes that hold that upper half
+            const uint32_t hi = wave_max_u32((uint32_t)(mine >> 32));
+            const uint32_t lo = wave_max_u32((uint32_t)(mine >> 32) == hi ? (uint32_t)mine : 0u);
+            best = ((unsigned long long)hi << 32) | lo;
+            // (the children are first looked at here, after the reductions: the empty
+            // statement keeps the compiler from waiting for them in their middle)
+            asm volatile("" : "+v"(e.dst) : "s"(hi), "s"(lo));
             const bool valid = e.dst != 0;
             const unsigned long long mask = __ballot(valid);
+            unsigned long long mine_new = 0;
             if (valid) {
                 const int pos = qn + __popcll(mask & ((1ull << lane) - 1ull));
                 const float pn = __fmul_rn(p, e.prob);
@@ -115,14 +125,17 @@ __global__ __launch_bounds__(64) void sam_tree_kernel(StaticView S, BatchView B,
                 qstate[pos] = e.dst;
                 qtok[pos] = (int32_t)e.token;
                 qpar[pos] = dn;
-                mine = key > mine ? key : mine;
+                mine_new = key;
             }
             if (lane == 0) qkey[idx] = 0;               // popped
-            // the largest 64-bit key: the largest upper half, then the largest lower
-            // half among the lanes that hold that upper half
-            const uint32_t hi = wave_max_u32((uint32_t)(mine >> 32));
-            const uint32_t lo = wave_max_u32((uint32_t)(mine >> 32) == hi ? (uint32_t)mine : 0u);
-            best = ((unsigned long long)hi << 32) | lo;
+            // A table row lists a state's successors by falling frequency, hence by falling
+            // probability (the product with p rounds monotonically), and is filled from its
+            // first entry on: the best of the new children is lane 0's, and among equal
+            // products it is also the one pushed first.
+            const unsigned long long first_new =
+                ((unsigned long long)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(mine_new >> 32)) << 32) |
+                (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)mine_new);
+            best = first_new > best ? first_new : best;
             qn += __popcll(mask);
             dn++;
             __syncthreads();
