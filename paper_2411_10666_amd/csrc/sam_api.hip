@@ -192,18 +192,24 @@ static int corpus_upload(sam_corpus *c)
             const uint64_t nb_new = (2 * (uint64_t)n_wide + 64 + kBucketSlots - 1) / kBucketSlots;
             if (e == hipSuccess && nb_new < h.n_buckets) {
                 const size_t b_new = (size_t)nb_new * kBucketSlots * sizeof(Slot);
-                e = hipMalloc(&d_new, b_new);
-                if (e == hipSuccess) e = launch_fill_empty(d_new, b_new, nullptr);
-                if (e == hipSuccess)
-                    e = launch_compact_slots((const Slot *)c->d_slots, (const uint32_t *)d_wide,
-                                             h.n_buckets * kBucketSlots, (Slot *)d_new, nb_new, nullptr);
-                if (e == hipSuccess) e = hipDeviceSynchronize();
-                if (e == hipSuccess) {
-                    (void)hipFree(c->d_slots);
-                    c->d_slots = d_new;
-                    n_buckets = nb_new;
-                } else if (d_new) {
-                    (void)hipFree(d_new);
+                if (hipMalloc(&d_new, b_new) != hipSuccess) {
+                    // no room for a second table beside the full one: the full one serves
+                    (void)hipGetLastError();
+                    d_new = nullptr;
+                } else {
+                    e = launch_fill_empty(d_new, b_new, nullptr);
+                    if (e == hipSuccess)
+                        e = launch_compact_slots((const Slot *)c->d_slots, (const uint32_t *)d_wide,
+                                                 h.n_buckets * kBucketSlots, (Slot *)d_new, nb_new,
+                                                 nullptr);
+                    if (e == hipSuccess) e = hipDeviceSynchronize();
+                    if (e == hipSuccess) {
+                        (void)hipFree(c->d_slots);
+                        c->d_slots = d_new;
+                        n_buckets = nb_new;
+                    } else {
+                        (void)hipFree(d_new);
+                    }
                 }
             }
         }
