@@ -83,7 +83,9 @@ const char *sam_build_id(void);
  * reports what stays afterwards).
  *   corpus_tokens : host, int32 [n_tokens]; a multi-document corpus is passed
  *                   already joined by a separator token (Section 3.1).
- *   n_tokens      : 1 .. 2^31-2.   vocab : 1 .. 2^31-1.
+ *   n_tokens      : 1 .. 2^31-2, and at most about 10^9: the host's transition
+ *                   table (4.29 slots per token) is indexed with 32 bits, a longer
+ *                   corpus is refused with SAM_EINVAL.   vocab : 1 .. 2^31-1.
  *   out           : receives the handle; free it with sam_corpus_free.
  * Synchronises.  Errors: SAM_EINVAL, SAM_ETOKEN (a corpus token outside the
  * vocabulary), SAM_ENOMEM, SAM_EDEVICE.
