@@ -538,7 +538,11 @@ def test_auxiliary_threshold_hook(l_threshold, l_bias):
 
 
 @pytest.mark.parametrize("seed,vocab,k,max_size", [(60, 2, 2, 40), (61, 3, 3, 16), (62, 6, 4, 70),
-                                                   (63, 32000, 4, 40), (64, 3, 8, 128), (65, 4, 1, 5)])
+                                                   (63, 32000, 4, 40), (64, 3, 8, 128), (65, 4, 1, 5),
+                                                   # equal frequencies everywhere (ties in the rows
+                                                   # and in the queue), full rows, the largest sizes
+                                                   (66, 2, 8, 128), (67, 8, 8, 128), (68, 5, 5, 100),
+                                                   (69, 12, 3, 128), (70, 2, 1, 128), (71, 300, 8, 60)])
 def test_tree_draft_matches_checker(seed, vocab, k, max_size):
     """Algorithm 4 on the GPU against the checker: tokens, parents, probability bits."""
     import torch
