@@ -404,6 +404,31 @@ def test_many_random_shapes(block):
         assert_same(g, r, has_static=use_corpus is not None)
 
 
+@pytest.mark.parametrize("vocab,n_corpus,B,T,A,L", [(1, 1, 1, 8, 1, 1), (1, 50, 2, 40, 3, 5),
+                                                   (2, 1, 1, 30, 1, 1), (2, 2, 3, 12, 2, 2),
+                                                   (5, 3, 1, 2, 1, 4)])
+def test_smallest_shapes(vocab, n_corpus, B, T, A, L):
+    """One-token alphabet (the text is a^n: every Expand but the first links to the state
+    before), one-token corpus, one sequence, rows and drafts of one token, capacity 2."""
+    rng = np.random.default_rng(vocab * 100 + n_corpus)
+    _say("smallest shapes vocab=%d corpus=%d B=%d T=%d A=%d L=%d" % (vocab, n_corpus, B, T, A, L))
+    corpus = rng.integers(0, vocab, size=n_corpus).astype(np.int32)
+    prompts = [rng.integers(0, vocab, size=int(rng.integers(0, 2))).astype(np.int32) for _ in range(B)]
+    steps = 4 * T
+    used = np.array([len(p) for p in prompts])
+    acc = rng.integers(0, vocab, size=(steps, B, A)).astype(np.int32)
+    counts = np.zeros((steps, B), dtype=np.int32)
+    for s_ in range(steps):
+        c = np.minimum(rng.integers(0, A + 1, size=B), T - used)
+        counts[s_] = c
+        used += c
+    g, status, _ = run_gpu(corpus, vocab, prompts, acc, counts, T, A, L)
+    r, _ = run_oracle(corpus, prompts, acc, counts, A, L)
+    assert status == 0
+    assert_same(g, r)
+    assert used.min() == T                   # every sequence filled to the last token
+
+
 def test_maximum_row_and_draft_sizes():
     """max_accept and draft_len at the largest values the library accepts."""
     B, T, A, L, steps, vocab = 3, 9000, 4096, 1024, 3, 3
