@@ -66,13 +66,13 @@ MEASURED_TRAFFIC = {
     # FETCH_SIZE mean 4145.76, WRITE_SIZE mean 995.16; the same counters read 131089.00
     # and 262144.00 for a copy kernel that reads and writes 262144 KiB, i.e. 2.000 and
     # 1.000 KiB per count: (4145.76 x 2.000 + 995.16) KiB = 9.510 MB per launch
-    "cfg5": {"bytes_per_match_step": 1176.7, "sources": "1d0923649a1aba54"},
+    "cfg5": {"bytes_per_match_step": 1176.7, "sources": "c150325d700c1347"},
     # config 3, 673 launches (1558.1 match-steps each): FETCH_SIZE 938.57 x 2.000 +
     # WRITE_SIZE 204.75 x 1.000 KiB = 2.132 MB per launch
-    "cfg3": {"bytes_per_match_step": 1368.3, "sources": "1d0923649a1aba54"},
+    "cfg3": {"bytes_per_match_step": 1368.3, "sources": "c150325d700c1347"},
     # config 4 (no corpus), 273 launches (7681.9 match-steps each): 2537.59 x 2.000 +
     # 1011.09 x 1.000 KiB = 6.232 MB per launch
-    "cfg4": {"bytes_per_match_step": 811.3, "sources": "1d0923649a1aba54"},
+    "cfg4": {"bytes_per_match_step": 811.3, "sources": "c150325d700c1347"},
 }
 
 KERNEL_SOURCES = ["sam_kernels.hip", "sam_layout.h", "sam_device.h"]

@@ -62,7 +62,8 @@ struct LinkPair {        // 8 B: what the host hands over per state
 // record is the next or next-but-one in this array -- so while a sequence follows
 // a stretch of the corpus, its lookups read consecutive records (four to a cache
 // line) instead of one random bucket each.  A state with at most two transitions
-// (most states: the deep ones) is answered by its record alone, hit or miss.
+// (most states: the deep ones) is answered by its record alone, hit or miss, and
+// the slot table the device keeps holds the transitions of the other states only.
 struct LinkRec {
     uint32_t itok;       // token of the first repeated transition, kNil = none
     uint32_t idst;       // its target
