@@ -3,9 +3,11 @@ pre-marshalled step plan, back-to-back launches on one stream, outputs of every
 step kept): the whole schedule of a benchmark workload is run through the HIP
 library and every output of every step is compared with the CPU checker.
 
-Progress lines are appended to a log file in the run's output folder (PROGRESS_DIR)
-so that a long, quiet test can be told from a hung one."""
+Progress lines go to the terminal as they come (past pytest's capture), and to a log
+file as well if SAM_TEST_PROGRESS_DIR names a folder, so that a long, quiet test can
+be told from a hung one."""
 import os
+import threading
 import time
 
 import numpy as np
@@ -16,15 +18,37 @@ from paper_2411_10666_amd.synth import CONFIGS, make_workload
 pytestmark = pytest.mark.gpu
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-PROGRESS_DIR = os.environ.get("SAM_TEST_PROGRESS_DIR", os.path.join(ROOT, "gpurun_out"))
+PROGRESS_DIR = os.environ.get("SAM_TEST_PROGRESS_DIR")      # also append the lines to a file there
+_live = None
+_say_lock = threading.Lock()
+
+
+@pytest.fixture(autouse=True)
+def _live_progress(capsys):
+    """These tests run for minutes: their progress lines go to the terminal as they come,
+    past pytest's capture, so that a watcher sees the run is alive."""
+    global _live
+    _live = capsys
+    yield
+    _live = None
 
 
 def _say(msg):
-    d = PROGRESS_DIR
-    os.makedirs(d, exist_ok=True)
-    with open(os.path.join(d, "test_progress.log"), "a") as f:
-        f.write("%s %s\n" % (time.strftime("%H:%M:%S"), msg))
-    print("[full] " + msg, flush=True)
+    with _say_lock:                      # the checker's build thread reports too
+        _say_locked(msg)
+
+
+def _say_locked(msg):
+    line = "%s [full] %s" % (time.strftime("%H:%M:%S"), msg)
+    if PROGRESS_DIR:
+        os.makedirs(PROGRESS_DIR, exist_ok=True)
+        with open(os.path.join(PROGRESS_DIR, "test_progress.log"), "a") as f:
+            f.write(line + "\n")
+    if _live is not None:
+        with _live.disabled():
+            print(line, flush=True)
+    else:
+        print(line, flush=True)
 
 
 def _gpu_schedule(w, sequences=None):
